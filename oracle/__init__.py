@@ -1,0 +1,34 @@
+"""CPU oracle for the rollout worker's generation path (test infrastructure).
+
+This package is the slow, plain reference that the HIP library is checked
+against.  It is test infrastructure only: nothing in the product package may
+import it, and it imports nothing from the product package.  Everything here
+is numpy on the host, float64 for the decoder arithmetic and exact integer /
+individually rounded float32 operations for the sampler.
+
+Modules
+-------
+decoder  -- the decoder-only policy pi_theta(a_t | q, a_<t) of Section 3.1:
+            one dense causal forward pass per prefix (the plain definition),
+            plus an incremental-KV variant used to prove the cache invariant.
+sampler  -- the specified sampling procedure that draws a_t and reports
+            log pi_behav(a_t | s_t) for the decoupled objective (Section 5.2).
+rollout  -- generate / update_weights semantics of the interruptible rollout
+            worker (Section 4.1) and the per-position policy versions of
+            Proposition 1.
+extras   -- the staleness gate (Section 5.1), the decoupled PPO objective
+            (Section 5.2) and the dynamic batching procedure (Appendix B.3).
+
+Pins (tests that tie each function to something other than itself) live in
+tests/test_oracle_*.py.  Parity status per function:
+
+decoder.rmsnorm, rope, attention, swiglu, forward  -- pinned (closed forms,
+    brute force, invariances).
+decoder whole-model values -- parity unpinned against the outside world: no
+    trained checkpoint or reference logits exist for this build; pinned only
+    through the invariants above on synthetic weights.
+sampler.philox4x32_10 -- pinned by the known-answer vectors distributed with
+    the generator's reference implementation (tests/golden/philox_kat.txt).
+sampler.sexp, mass, nucleus, draw, logprobs -- pinned (libm, exact integer
+    identities, brute-force sort, chi-square on empirical frequencies).
+"""
