@@ -1,0 +1,190 @@
+/*
+ * areal.h -- C boundary of the MI355X rollout-generation library.
+ *
+ * The library implements the rollout worker of the AReaL paper (Section 4.1):
+ * batched autoregressive generation of a decoder-only policy over many
+ * variable-length sequences (`generate`), and the in-flight weight update
+ * that interrupts it (`update_weights`).  Every sampled token comes with the
+ * log-probability the sampling policy gave it, log pi_behav(a_t | s_t), which
+ * the decoupled PPO objective (Section 5.2, Eq. 4-5) divides by, and with the
+ * version of the policy that produced it (Proposition 1: the behaviour
+ * policy of an interrupted trajectory is defined position by position).
+ *
+ *   generate        = areal_prefill, then repeat { areal_sample_logprob,
+ *                     areal_decode_step } until the caller ends the sequence
+ *                     with areal_free_seq
+ *   update_weights  = areal_update_weights_interrupt
+ *
+ * Conventions
+ *  - Plain C ABI, no exceptions, no abort.  Every call returns AREAL_OK (0)
+ *    or a negative error code; areal_last_error() gives the text.  A call
+ *    that fails leaves the context as it was before the call.
+ *  - "device" pointers are HIP device memory owned by the caller (in the
+ *    tests and benchmark: PyTorch allocations); "host" pointers are ordinary
+ *    process memory, read or written before the call returns.
+ *  - All device work is enqueued on the caller's stream (areal_model_cfg.
+ *    hip_stream) in call order.  Calls return without waiting for the GPU;
+ *    outputs in device memory are valid once the stream reaches that point.
+ *  - One context serves one GPU and is not thread safe.
+ *  - Matrices are row-major, out-features major: y = x W^T with W [out, in].
+ *  - The model is the Qwen2 family: pre-norm blocks, RMSNorm, rotary position
+ *    embedding in rotate-half pairing, grouped-query causal attention,
+ *    SwiGLU feed-forward, untied (or aliased) output projection.
+ */
+#ifndef AREAL_H
+#define AREAL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AREAL_OK        0
+#define AREAL_E_INVAL  (-1)  /* bad argument: NULL, shape, unknown or duplicate sequence id      */
+#define AREAL_E_NOMEM  (-2)  /* KV arena, workspace or a per-sequence limit exhausted            */
+#define AREAL_E_STATE  (-3)  /* call out of order: no weights, decode before prefill, version
+                                not increasing                                                   */
+#define AREAL_E_HIP    (-4)  /* the HIP runtime reported an error                                */
+
+#define AREAL_DTYPE_F32   0
+#define AREAL_DTYPE_BF16  1
+
+#define AREAL_KV_BLOCK_TOKENS 16
+
+typedef struct areal_ctx areal_ctx;   /* opaque; owned by the library */
+
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float   rope_theta;          /* rotary base (1e6 for the Qwen2 shapes)                 */
+  float   rms_eps;             /* added to the mean square inside the root (1e-6)         */
+  int32_t max_seqs;            /* sequence ids are 0 .. max_seqs-1                        */
+  int32_t max_seq_len;         /* prompt + generated tokens per sequence                  */
+  int32_t max_batch_tokens;    /* rows of one forward pass; longer prefills are chunked   */
+  int32_t fp32_weights;        /* 1: areal_load_weights may be given float32 parameters,
+                                  which the library rounds to bf16 (nearest even) into
+                                  space reserved in the workspace                         */
+  void*    kv_arena;           /* device; paged K/V pool, any size >= one block           */
+  uint64_t kv_arena_bytes;
+  void*    workspace;          /* device; >= areal_workspace_bytes(cfg), 256-B aligned    */
+  uint64_t workspace_bytes;
+  void*    hip_stream;         /* hipStream_t owned by the caller; NULL = default stream  */
+} areal_model_cfg;
+
+/* One parameter set.  All pointers are device pointers that stay valid and
+ * unchanged until the next areal_load_weights / areal_update_weights_interrupt
+ * has been called AND the stream has passed it (the library reads them in
+ * place; with dtype F32 it reads them only during that call's conversion).
+ * Per-layer arrays are host arrays of n_layers device pointers. */
+typedef struct {
+  int32_t dtype;                                    /* AREAL_DTYPE_BF16 or AREAL_DTYPE_F32   */
+  const void *embed;                                /* [vocab, hidden]                       */
+  const void *lm_head;                              /* [vocab, hidden]; may equal embed      */
+  const void *final_norm;                           /* [hidden]                              */
+  const void *const *wq, *const *wk, *const *wv;    /* [nq*d, hidden], [nkv*d, hidden] x2    */
+  const void *const *wo;                            /* [hidden, nq*d]                        */
+  const void *const *wgate, *const *wup;            /* [ffn, hidden]                         */
+  const void *const *wdown;                         /* [hidden, ffn]                         */
+  const void *const *norm_attn, *const *norm_ffn;   /* [hidden]                              */
+  const void *const *bq, *const *bk, *const *bv;    /* [nq*d], [nkv*d] x2; NULL = no bias    */
+} areal_weights;
+
+/* Bytes of workspace a context with this configuration needs (0 if the
+ * configuration is invalid).  Bytes of one 16-token KV block over all layers. */
+uint64_t areal_workspace_bytes(const areal_model_cfg* cfg);
+uint64_t areal_kv_block_bytes(const areal_model_cfg* cfg);
+
+int areal_create(const areal_model_cfg* cfg, areal_ctx** out);
+int areal_destroy(areal_ctx* ctx);          /* waits for the stream, frees host state only */
+const char* areal_last_error(const areal_ctx* ctx);   /* ctx may be NULL: last create error */
+
+/* Section 4.1 "loads parameters of new versions": register the parameter set
+ * every later forward pass uses.  Allowed only while no sequence is live (with
+ * live sequences use areal_update_weights_interrupt).  `version` tags the
+ * tokens sampled from logits computed under this set. */
+int areal_load_weights(areal_ctx* ctx, const areal_weights* w, uint64_t version);
+
+/* Section 4.1 `generate`, first half; Section 3.1 state s_1 = q.  Starts n_seqs
+ * new sequences: reserves KV blocks, runs the decoder over the packed prompt
+ * tokens with causal attention (in chunks of max_batch_tokens rows), stores K
+ * and V in the paged cache, and writes the logits for each sequence's first
+ * generated token.
+ *   seq_ids    host [n_seqs]   unused ids in 0 .. max_seqs-1, all distinct
+ *   tokens     host [cu_seqlens[n_seqs]]  packed prompts, each length >= 1
+ *   cu_seqlens host [n_seqs+1] prefix sums of the prompt lengths, [0] = 0
+ *   logits_out device float32 [n_seqs, vocab] */
+int areal_prefill(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
+                  const int32_t* tokens, const int32_t* cu_seqlens, float* logits_out);
+
+/* Section 3.1 transition s_{t+1} = concat(s_t, a_t); Section 4.1 `generate`,
+ * the decoding loop.  Appends tokens_in[i] to sequence seq_ids[i] and runs one
+ * forward pass at one row per sequence against each sequence's own cached K/V.
+ *   seq_ids   host [n_seqs]    live, distinct
+ *   tokens_in device int32 [n_seqs]  (typically tokens_out of the sampler)
+ *   logits_out device float32 [n_seqs, vocab]  logits for the NEXT token
+ * The appended token is tagged with the version whose logits it was sampled
+ * from (the version loaded when those logits were computed). */
+int areal_decode_step(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
+                      const int32_t* tokens_in, float* logits_out);
+
+/* Section 5.2: pi_behav is the policy used for sampling; Table 3 defaults
+ * temperature 1, top-p 1, top-k off.  For each row of float32 logits:
+ *   z = logits * (1/T); fixed-point masses c_i = floor(sexp(z_i - max z) * 2^32);
+ *   nucleus = shortest prefix, ranked by (c desc, id asc), whose mass reaches
+ *   ceil(top_p * sum c); r = floor(R * S_nuc / 2^64) with R the first two words
+ *   of Philox4x32-10(counter=(position, seq_id, 0, 0), key=seed); the token is
+ *   the first kept id, ascending, whose running mass exceeds r.
+ *   logp_behav = log(c_tok / S_nuc); logp_full = log_softmax(z)[tok].
+ * The token id is a pure function of (logits row, T, top_p, seed, seq_id,
+ * position).  Logits must be finite.
+ *   logits    device float32 [n, vocab]
+ *   seq_ids, positions  host [n]  (position = index the sampled token will have)
+ *   forced_tokens  device int32 [n] or NULL.  Given: no draw; tokens_out =
+ *                  forced_tokens and the log-probs are those of the forced
+ *                  tokens (-inf behaviour log-prob outside the nucleus).
+ *   tokens_out device int32 [n]; logp_behav_out device float32 [n];
+ *   logp_full_out device float32 [n] or NULL.
+ * T <= 0, top_p <= 0 or NaN -> AREAL_E_INVAL. */
+int areal_sample_logprob(areal_ctx* ctx, int32_t n, const float* logits,
+                         const int32_t* seq_ids, const int32_t* positions,
+                         float temperature, float top_p, uint64_t philox_seed,
+                         const int32_t* forced_tokens,
+                         int32_t* tokens_out, float* logp_behav_out, float* logp_full_out);
+
+/* Section 4.1 `update_weights`: interrupt all generations in flight, switch to
+ * the new parameters, discard the K/V computed with the old ones and recompute
+ * them: every live sequence's whole prefix (prompt + tokens generated so far)
+ * is prefilled again under new_w.  Tokens already emitted, and their version
+ * tags, are untouched (Proposition 1).  new_version > the current version.
+ *   n_live_out        host int32          number of live sequences
+ *   live_seq_ids_out  host int32 [max_seqs]  their ids, ascending
+ *   logits_out        device float32 [n_live, vocab] in that order; may be
+ *                     NULL only if no sequence is live
+ *   reprefilled_tokens_out  host int64 or NULL: prefix tokens recomputed */
+int areal_update_weights_interrupt(areal_ctx* ctx, const areal_weights* new_w,
+                                   uint64_t new_version, int32_t* n_live_out,
+                                   int32_t* live_seq_ids_out, float* logits_out,
+                                   int64_t* reprefilled_tokens_out);
+
+/* Termination (Section 4.1 "until the next interruption or termination"): the
+ * caller decides when a sequence ends; its KV blocks return to the pool. */
+int areal_free_seq(areal_ctx* ctx, int32_t seq_id);
+
+/* Host-side state queries.  areal_get_tokens waits for the stream. */
+int areal_seq_len(areal_ctx* ctx, int32_t seq_id, int32_t* len_out);   /* -1 if not live */
+int areal_get_tokens(areal_ctx* ctx, int32_t seq_id, int32_t* tokens_out /* host [len] */);
+/* Policy version per position: -1 for prompt tokens, else the version that
+ * produced the token (Proposition 1). */
+int areal_get_versions(areal_ctx* ctx, int32_t seq_id, int64_t* versions_out /* host [len] */);
+int areal_kv_blocks(areal_ctx* ctx, int64_t* total_out, int64_t* free_out);
+
+/* Benchmark helper: make `seq_id` a live sequence of `len` tokens whose K/V are
+ * taken to be whatever the arena blocks assigned to it already hold and whose
+ * token history is `fill_token`.  No forward pass runs.  Lets a decode step be
+ * timed at a chosen context depth without generating up to it. */
+int areal_adopt_seq(areal_ctx* ctx, int32_t seq_id, int32_t len, int32_t fill_token);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AREAL_H */

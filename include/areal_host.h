@@ -1,0 +1,47 @@
+/*
+ * areal_host.h -- host-only entry points of the library: the paged KV block
+ * allocator and the pass planner, exposed so that they can be exercised
+ * without a GPU.  They are the same objects the generation calls of areal.h
+ * use internally (KV cache management is named by the paper, Section 2 "LLM
+ * Training and Inference", as a requirement of generation; the token budget
+ * per pass follows the padding-free packing of Section 6).
+ * None of these functions touches the GPU.
+ */
+#ifndef AREAL_HOST_H
+#define AREAL_HOST_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct areal_kvalloc areal_kvalloc;
+
+/* A pool of n_blocks blocks of 16 tokens for sequences 0 .. max_seqs-1.
+ * Returns NULL on invalid arguments.  The caller destroys it. */
+areal_kvalloc* areal_kvalloc_create(int64_t n_blocks, int32_t max_seqs, int32_t max_blocks_per_seq);
+void areal_kvalloc_destroy(areal_kvalloc* a);
+/* Grow sequence `seq` so that it can hold n_tokens.  0 on success; AREAL_E_NOMEM
+ * (and no change) if the pool or the per-sequence limit is too small. */
+int areal_kvalloc_reserve(areal_kvalloc* a, int32_t seq, int64_t n_tokens);
+/* Return all blocks of `seq` to the pool. */
+void areal_kvalloc_release(areal_kvalloc* a, int32_t seq);
+int64_t areal_kvalloc_free_blocks(const areal_kvalloc* a);
+/* Copy up to `cap` block ids of `seq` into out (host); returns the block count. */
+int32_t areal_kvalloc_table(const areal_kvalloc* a, int32_t seq, int32_t* out, int32_t cap);
+/* Deterministically permute the free list (block placement must not matter). */
+void areal_kvalloc_shuffle(areal_kvalloc* a, uint64_t seed);
+
+/* Cut n_spans sequences of the given lengths (each starting at position 0)
+ * into forward passes of at most max_rows rows, in order.  Writes up to `cap`
+ * records of 6 int32 {pass, span, pos0, len, row0, out_index} to out (host)
+ * and returns the number of records; out_index is the span index on the piece
+ * that ends a span, else -1. */
+int32_t areal_plan_passes(int32_t n_spans, const int32_t* lens, int32_t max_rows, int32_t* out,
+                          int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AREAL_HOST_H */

@@ -1,0 +1,57 @@
+// Shared device-side types and small helpers for the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace areal {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short  s16x4 __attribute__((ext_vector_type(4)));
+typedef float  f32x4 __attribute__((ext_vector_type(4)));
+typedef float  f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+constexpr int kBlockTokens = 16;   // tokens per KV block
+
+__device__ __forceinline__ float bf2f(bf16 x) { return (float)x; }
+__device__ __forceinline__ bf16 f2bf(float x) { return (bf16)x; }   // round to nearest even
+
+// 16-byte global load of 8 bf16
+__device__ __forceinline__ bf16x8 ld8(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+
+// ---- paged KV arena addressing --------------------------------------------
+// arena = [layer][block][kv_head][K tile | V tile], tiles of 16*d bf16.
+//   K tile: [token 0..15][d]                       (row-major)
+//   V tile: [lane 0..63][n 0..d/16-1][t 0..3] with lane = g*16 + j holding
+//           V[token 4g+t][dim 16n+j]: exactly the B operand of the 16x16x16
+//           MFMA that multiplies probabilities by values, 64 B per lane.
+struct KvGeom {
+  int n_kv_heads, head_dim;
+  int64_t layer_stride;   // elements between layers = n_blocks * block_stride
+  int block_stride;       // elements per block of one layer = n_kv_heads * 2 * 16 * d
+};
+__device__ __forceinline__ int64_t kv_tile_off(const KvGeom& g, int block, int kvh, int is_v) {
+  return (int64_t)block * g.block_stride + (int64_t)(kvh * 2 + is_v) * (kBlockTokens * g.head_dim);
+}
+__device__ __forceinline__ int v_tile_index(int head_dim, int token, int dim) {
+  int g = token >> 2, t = token & 3, n = dim >> 4, j = dim & 15;
+  return (((g * 16 + j) * (head_dim >> 4)) + n) * 4 + t;
+}
+
+}  // namespace areal

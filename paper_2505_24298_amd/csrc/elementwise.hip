@@ -1,0 +1,156 @@
+// Small HBM-bound kernels of the decoder block: token embedding, RMSNorm,
+// rotary embedding + paged K/V store, float32 -> bf16 conversion.
+#include "kernels.hpp"
+
+namespace areal {
+
+// h[r,:] = E[token(r),:] as float32.  In a decode step (tokens_in != null) the
+// kernel also records the appended token in the history and installs the KV
+// block the host reserved for a sequence that crossed a block boundary.
+__global__ __launch_bounds__(256) void embed_kernel(const bf16* __restrict__ E, int H, int V,
+                                                    RowMeta rm, const int32_t* __restrict__ tokens_in,
+                                                    const int32_t* __restrict__ new_block, SeqState st,
+                                                    float* __restrict__ h) {
+  const int r = blockIdx.x;
+  const int slot = rm.slot[r], pos = rm.pos[r];
+  int tok;
+  int32_t* hp = st.hist + (int64_t)slot * st.max_seq_len + pos;
+  if (tokens_in) {
+    tok = tokens_in[r];
+    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+    if (threadIdx.x == 0) *hp = tok;
+  } else {
+    tok = *hp;
+  }
+  if (new_block && threadIdx.x == 0) {
+    int nb = new_block[r];
+    if (nb >= 0) st.table[(int64_t)slot * st.max_blocks + pos / kBlockTokens] = nb;
+  }
+  const bf16* src = E + (int64_t)tok * H;
+  float* dst = h + (int64_t)r * H;
+  for (int c = threadIdx.x * 8; c < H; c += 256 * 8) {
+    bf16x8 v = ld8(src + c);
+    f32x4 a = {bf2f(v[0]), bf2f(v[1]), bf2f(v[2]), bf2f(v[3])};
+    f32x4 b = {bf2f(v[4]), bf2f(v[5]), bf2f(v[6]), bf2f(v[7])};
+    *reinterpret_cast<f32x4*>(dst + c) = a;
+    *reinterpret_cast<f32x4*>(dst + c + 4) = b;
+  }
+}
+
+hipError_t launch_embed(hipStream_t s, const bf16* embed, int hidden, int vocab, int M, RowMeta rm,
+                        const int32_t* tokens_in, const int32_t* new_block, SeqState st, float* h) {
+  if (M <= 0 || hidden % 8 || vocab <= 0) return hipErrorInvalidValue;
+  embed_kernel<<<M, 256, 0, s>>>(embed, hidden, vocab, rm, tokens_in, new_block, st, h);
+  return hipGetLastError();
+}
+
+// y = x / sqrt(mean(x^2) + eps) * gain, one wavefront per row, bf16 out.
+// src_rows (optional) gathers: output row r is computed from input row src_rows[r].
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x,
+                                                      const bf16* __restrict__ gain,
+                                                      bf16* __restrict__ y, int M, int H, float eps,
+                                                      const int32_t* __restrict__ src_rows) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int src = src_rows ? src_rows[row] : row;
+  const float* xp = x + (int64_t)src * H;
+  float ss = 0.f;
+  for (int c = lane * 4; c < H; c += 256) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(xp + c);
+    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+  }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)H + eps);
+  bf16* yp = y + (int64_t)row * H;
+  for (int c = lane * 4; c < H; c += 256) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(xp + c);
+    bf16x4 g = *reinterpret_cast<const bf16x4*>(gain + c);
+    bf16x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = f2bf(v[i] * r * bf2f(g[i]));
+    *reinterpret_cast<bf16x4*>(yp + c) = o;
+  }
+}
+
+hipError_t launch_rmsnorm(hipStream_t s, const float* x, const bf16* gain, bf16* y, int M, int hidden,
+                          float eps, const int32_t* src_rows) {
+  if (M <= 0 || hidden % 4) return hipErrorInvalidValue;
+  rmsnorm_kernel<<<(M + 3) / 4, 256, 0, s>>>(x, gain, y, M, hidden, eps, src_rows);
+  return hipGetLastError();
+}
+
+// Adds the optional QKV bias, rotates q and k heads (rotate-half pairing: dims
+// j and j + d/2 turn by pos * theta^(-2j/d), angles from a host-built table),
+// writes q as bf16 [M, nq, d] and stores k, v into the sequence's KV block.
+__global__ __launch_bounds__(256) void rope_kvwrite_kernel(
+    const float* __restrict__ qkv, RowMeta rm, SeqState st, const bf16* __restrict__ bq,
+    const bf16* __restrict__ bk, const bf16* __restrict__ bv, const float* __restrict__ cos_tab,
+    const float* __restrict__ sin_tab, bf16* __restrict__ q_out, bf16* __restrict__ arena_layer,
+    KvGeom geom, int nq) {
+  const int r = blockIdx.x;
+  const int d = geom.head_dim, half = d >> 1, nkv = geom.n_kv_heads;
+  const int slot = rm.slot[r], pos = rm.pos[r];
+  const int blk = st.table[(int64_t)slot * st.max_blocks + pos / kBlockTokens];
+  const int tin = pos % kBlockTokens;
+  const int ld = (nq + 2 * nkv) * d;
+  const float* row = qkv + (int64_t)r * ld;
+  const float* ct = cos_tab + (int64_t)pos * half;
+  const float* sn = sin_tab + (int64_t)pos * half;
+  const int n_rot = (nq + nkv) * half;
+  for (int idx = threadIdx.x; idx < n_rot; idx += 256) {
+    const int head = idx / half, j = idx - head * half;
+    float x1 = row[head * d + j], x2 = row[head * d + j + half];
+    if (bq) {
+      const bf16* b = head < nq ? bq + head * d : bk + (head - nq) * d;
+      x1 += bf2f(b[j]);
+      x2 += bf2f(b[j + half]);
+    }
+    const float c = ct[j], sv = sn[j];
+    const float y1 = x1 * c - x2 * sv, y2 = x2 * c + x1 * sv;
+    if (head < nq) {
+      bf16* qo = q_out + ((int64_t)r * nq + head) * d;
+      qo[j] = f2bf(y1);
+      qo[j + half] = f2bf(y2);
+    } else {
+      bf16* kt = arena_layer + kv_tile_off(geom, blk, head - nq, 0) + tin * d;
+      kt[j] = f2bf(y1);
+      kt[j + half] = f2bf(y2);
+    }
+  }
+  const float* vrow = row + (nq + nkv) * d;
+  for (int idx = threadIdx.x; idx < nkv * d; idx += 256) {
+    const int kvh = idx / d, dim = idx - kvh * d;
+    float v = vrow[idx];
+    if (bv) v += bf2f(bv[idx]);
+    bf16* vt = arena_layer + kv_tile_off(geom, blk, kvh, 1);
+    vt[v_tile_index(d, tin, dim)] = f2bf(v);
+  }
+}
+
+hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
+                               const bf16* bq, const bf16* bk, const bf16* bv, const float* cos_tab,
+                               const float* sin_tab, bf16* q_out, bf16* arena_layer, KvGeom geom,
+                               int n_q_heads) {
+  if (M <= 0 || geom.head_dim % 16 || (bq && (!bk || !bv))) return hipErrorInvalidValue;
+  rope_kvwrite_kernel<<<M, 256, 0, s>>>(qkv, rm, st, bq, bk, bv, cos_tab, sin_tab, q_out, arena_layer,
+                                        geom, n_q_heads);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ src,
+                                                          bf16* __restrict__ dst, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (; i < n; i += stride) dst[i] = f2bf(src[i]);
+}
+
+hipError_t launch_f32_to_bf16(hipStream_t s, const float* src, bf16* dst, int64_t n) {
+  if (n <= 0) return hipErrorInvalidValue;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  f32_to_bf16_kernel<<<(int)blocks, 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+
+}  // namespace areal

@@ -1,0 +1,65 @@
+// Host-callable launchers of the gfx950 kernels (internal C++ interface; the
+// public boundary is include/areal.h).  Every launcher validates the shapes
+// its kernel assumes and returns hipErrorInvalidValue instead of launching
+// when they do not hold.
+#pragma once
+#include "common.hpp"
+
+namespace areal {
+
+// ---- elementwise.hip --------------------------------------------------------
+struct RowMeta {               // device arrays, one entry per row of the pass
+  const int32_t* slot;         // sequence slot of the row
+  const int32_t* pos;          // absolute position of the row's token
+};
+struct SeqState {              // device-resident per-sequence state
+  int32_t* hist;               // [max_seqs][max_seq_len] token history
+  int32_t* table;              // [max_seqs][max_blocks] KV block ids
+  int max_seq_len, max_blocks;
+};
+
+hipError_t launch_embed(hipStream_t s, const bf16* embed, int hidden, int vocab, int M, RowMeta rm,
+                        const int32_t* tokens_in, const int32_t* new_block, SeqState st, float* h);
+hipError_t launch_rmsnorm(hipStream_t s, const float* x, const bf16* gain, bf16* y, int M, int hidden,
+                          float eps, const int32_t* src_rows);
+hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
+                               const bf16* bq, const bf16* bk, const bf16* bv, const float* cos_tab,
+                               const float* sin_tab, bf16* q_out, bf16* arena_layer, KvGeom geom,
+                               int n_q_heads);
+hipError_t launch_f32_to_bf16(hipStream_t s, const float* src, bf16* dst, int64_t n);
+
+// ---- gemm.hip ---------------------------------------------------------------
+// C[M,N] (+)= A[M,K] * W[N,K]^T, bf16 inputs, float32 accumulation on MFMA.
+// W may be up to three row-segments (e.g. wq | wk | wv), each [rows, K].
+struct GemmW {
+  const bf16* ptr[3];
+  int end[3];                  // cumulative row counts; end[last used] == N
+};
+enum GemmMode {
+  GEMM_STORE_F32 = 0,          // C float32 = acc
+  GEMM_ADD_F32 = 1,            // C float32 += acc            (residual update)
+  GEMM_SWIGLU_BF16 = 2,        // two W of [N,K] (gate, up): C bf16 = silu(A gate^T) * (A up^T)
+};
+hipError_t launch_gemm(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
+                       GemmMode mode);
+
+// ---- attention.hip ----------------------------------------------------------
+struct AttnWork {              // prefill work item: 64 query rows of one sequence
+  int32_t slot, row0, pos0, n_rows;
+};
+// decode: one query row per sequence (row i <-> rm.slot[i], rm.pos[i]); context
+// = pos+1 tokens.  `chunk` tokens per split (multiple of 64); partial results go
+// through `part_o` / `part_ml` when n_splits > 1.
+hipError_t launch_attn_decode(hipStream_t s, const bf16* q, int M, RowMeta rm, SeqState st,
+                              const bf16* arena_layer, KvGeom geom, int n_q_heads, int chunk,
+                              int n_splits, float* part_o, float* part_ml, bf16* out);
+hipError_t launch_attn_prefill(hipStream_t s, const bf16* q, const AttnWork* work, int n_work,
+                               SeqState st, const bf16* arena_layer, KvGeom geom, int n_q_heads,
+                               bf16* out);
+
+// ---- sampler.hip ------------------------------------------------------------
+hipError_t launch_sampler(hipStream_t s, int n, int vocab, const float* logits, const int32_t* seq_ids,
+                          const int32_t* positions, float inv_temperature, float top_p, uint64_t seed,
+                          const int32_t* forced, int32_t* tokens_out, float* logp_behav, float* logp_full);
+
+}  // namespace areal

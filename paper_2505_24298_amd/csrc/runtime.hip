@@ -1,0 +1,728 @@
+// Host runtime behind include/areal.h: context, sequence table, per-pass
+// metadata staging, kernel sequencing of one decoder forward pass, and the
+// five boundary calls.  All device work goes to the caller's stream.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/areal.h"
+#include "../../include/areal_host.h"
+#include "kernels.hpp"
+#include "kv_alloc.hpp"
+
+using namespace areal;
+
+namespace {
+
+constexpr int kMaxSplits = 32;
+constexpr int kRingSegs = 8;
+
+thread_local std::string g_create_error;
+
+inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {                     // byte offsets into the workspace
+  uint64_t h, xn, qkv, q, attn, act, xlast, part_o, part_ml, hist, table, cos_t, sin_t, ring, wconv,
+      total;
+  uint64_t ring_bytes, wconv_elems;
+  int max_blocks;
+};
+
+bool cfg_valid(const areal_model_cfg* c, std::string* why) {
+  auto bad = [&](const char* m) { if (why) *why = m; return false; };
+  if (!c) return bad("cfg is NULL");
+  if (c->n_layers <= 0 || c->hidden <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->ffn <= 0 ||
+      c->vocab <= 0)
+    return bad("non-positive model dimension");
+  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return bad("head_dim must be 32, 64 or 128");
+  if (c->n_q_heads % c->n_kv_heads || c->n_q_heads / c->n_kv_heads > 16)
+    return bad("n_q_heads must be a multiple of n_kv_heads with at most 16 query heads per KV head");
+  if (c->hidden % 8 || c->ffn % 8) return bad("hidden and ffn must be multiples of 8");
+  if ((int64_t)c->vocab > 262144) return bad("vocab above 262144");
+  if (c->max_seqs <= 0 || c->max_seq_len <= 0 || c->max_batch_tokens < c->max_seqs)
+    return bad("need max_seqs > 0, max_seq_len > 0, max_batch_tokens >= max_seqs");
+  if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return bad("bad rope_theta / rms_eps");
+  return true;
+}
+
+uint64_t total_params(const areal_model_cfg& c) {
+  const uint64_t H = c.hidden, F = c.ffn, qd = (uint64_t)c.n_q_heads * c.head_dim,
+                 kd = (uint64_t)c.n_kv_heads * c.head_dim, V = c.vocab;
+  const uint64_t per_layer = qd * H + 2 * kd * H + H * qd + 2 * F * H + H * F + 2 * H + qd + 2 * kd;
+  return 2 * V * H + H + (uint64_t)c.n_layers * per_layer + 64 * (uint64_t)(c.n_layers * 12 + 3);
+}
+
+Layout make_layout(const areal_model_cfg& c) {
+  Layout L{};
+  const uint64_t M = c.max_batch_tokens, H = c.hidden, d = c.head_dim;
+  const uint64_t qd = (uint64_t)c.n_q_heads * d, kd = (uint64_t)c.n_kv_heads * d;
+  uint64_t off = 0;
+  auto take = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, 256); return o; };
+  L.h = take(M * H * 4);
+  L.xn = take(M * H * 2);
+  L.qkv = take(M * (qd + 2 * kd) * 4);
+  L.q = take(M * qd * 2);
+  L.attn = take(M * qd * 2);
+  L.act = take(M * (uint64_t)c.ffn * 2);
+  L.xlast = take((uint64_t)c.max_seqs * H * 2);
+  L.part_o = take((uint64_t)c.max_seqs * c.n_q_heads * kMaxSplits * d * 4);
+  L.part_ml = take((uint64_t)c.max_seqs * c.n_q_heads * kMaxSplits * 2 * 4);
+  L.max_blocks = (c.max_seq_len + AREAL_KV_BLOCK_TOKENS - 1) / AREAL_KV_BLOCK_TOKENS;
+  L.hist = take((uint64_t)c.max_seqs * c.max_seq_len * 4);
+  L.table = take((uint64_t)c.max_seqs * L.max_blocks * 4);
+  L.cos_t = take((uint64_t)c.max_seq_len * (d / 2) * 4);
+  L.sin_t = take((uint64_t)c.max_seq_len * (d / 2) * 4);
+  // per pass: slot, pos, token, new_block per row + work items + last rows
+  const uint64_t per_pass = M * 16 + (M / 64 + 2 * (uint64_t)c.max_seqs + 64) * 16 + (uint64_t)c.max_seqs * 16;
+  L.ring_bytes = align_up(std::max<uint64_t>(per_pass * 2, 1u << 20), 4096) * kRingSegs;
+  L.ring = take(L.ring_bytes);
+  L.wconv_elems = c.fp32_weights ? total_params(c) : 0;
+  L.wconv = take(L.wconv_elems * 2);
+  L.total = off;
+  return L;
+}
+
+struct SeqInfo {
+  bool live = false;
+  int32_t len = 0;
+  int64_t pending_version = 0;          // version whose logits the next token is sampled from
+  std::vector<int64_t> versions;        // per position; -1 = prompt
+};
+
+struct WeightSet {
+  const bf16 *embed = nullptr, *lm_head = nullptr, *final_norm = nullptr;
+  std::vector<const bf16*> wq, wk, wv, wo, wgate, wup, wdown, norm_attn, norm_ffn, bq, bk, bv;
+  bool has_bias = false;
+};
+
+}  // namespace
+
+struct areal_ctx {
+  areal_model_cfg cfg;
+  Layout lay;
+  hipStream_t stream;
+  char* ws;
+  KvGeom geom;
+  int64_t n_blocks;
+  KvAllocator* alloc = nullptr;
+  std::vector<SeqInfo> seqs;
+  WeightSet w;
+  bool have_weights = false;
+  int64_t version = 0;
+  // metadata ring: pinned host mirror of a device ring, reused segment by segment
+  char* ring_host = nullptr;
+  uint64_t seg_bytes = 0, seg_used = 0;
+  int seg = 0;
+  hipEvent_t seg_done[kRingSegs];
+  bool seg_recorded[kRingSegs];
+  std::string err;
+
+  template <class T> T* wsp(uint64_t off) const { return reinterpret_cast<T*>(ws + off); }
+  SeqState seq_state() const {
+    return SeqState{wsp<int32_t>(lay.hist), wsp<int32_t>(lay.table), cfg.max_seq_len, lay.max_blocks};
+  }
+};
+
+namespace {
+
+int fail(areal_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_create_error = msg;
+  return code;
+}
+#define HIP_TRY(ctx, expr)                                                                        \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess)                                                                         \
+      return fail(ctx, AREAL_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));           \
+  } while (0)
+
+// ---- metadata staging -------------------------------------------------------
+// Reserve `bytes` in the ring (host pointer returned, device address in *dev).
+// A pass stages everything it needs, then calls ring_flush once.
+struct Staged { char* host; char* dev; };
+
+int ring_begin(areal_ctx* c, uint64_t bytes_needed) {
+  if (bytes_needed > c->seg_bytes) return fail(c, AREAL_E_NOMEM, "metadata for one pass exceeds a ring segment");
+  if (c->seg_used + bytes_needed > c->seg_bytes) {
+    HIP_TRY(c, hipEventRecord(c->seg_done[c->seg], c->stream));
+    c->seg_recorded[c->seg] = true;
+    c->seg = (c->seg + 1) % kRingSegs;
+    c->seg_used = 0;
+    if (c->seg_recorded[c->seg]) HIP_TRY(c, hipEventSynchronize(c->seg_done[c->seg]));
+  }
+  return AREAL_OK;
+}
+Staged ring_take(areal_ctx* c, uint64_t bytes) {
+  const uint64_t off = (uint64_t)c->seg * c->seg_bytes + c->seg_used;
+  c->seg_used += align_up(bytes, 64);
+  return Staged{c->ring_host + off, c->ws + c->lay.ring + off};
+}
+int ring_flush(areal_ctx* c, uint64_t start_used) {
+  const uint64_t off = (uint64_t)c->seg * c->seg_bytes + start_used;
+  const uint64_t n = c->seg_used - start_used;
+  if (n == 0) return AREAL_OK;
+  HIP_TRY(c, hipMemcpyAsync(c->ws + c->lay.ring + off, c->ring_host + off, n, hipMemcpyHostToDevice, c->stream));
+  return AREAL_OK;
+}
+
+// ---- weights ----------------------------------------------------------------
+bool weights_complete(const areal_ctx* c, const areal_weights* w) {
+  if (!w || !w->embed || !w->lm_head || !w->final_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
+      !w->wgate || !w->wup || !w->wdown || !w->norm_attn || !w->norm_ffn)
+    return false;
+  const bool bias = w->bq || w->bk || w->bv;
+  if (bias && !(w->bq && w->bk && w->bv)) return false;
+  for (int l = 0; l < c->cfg.n_layers; ++l) {
+    if (!w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->wgate[l] || !w->wup[l] ||
+        !w->wdown[l] || !w->norm_attn[l] || !w->norm_ffn[l])
+      return false;
+    if (bias && (!w->bq[l] || !w->bk[l] || !w->bv[l])) return false;
+  }
+  return true;
+}
+
+// Install `w` as the current parameter set (bf16: borrow in place; f32: round
+// into the workspace copy, stream-ordered after all earlier passes).
+int install_weights(areal_ctx* c, const areal_weights* w) {
+  const areal_model_cfg& g = c->cfg;
+  const int L = g.n_layers;
+  const uint64_t H = g.hidden, F = g.ffn, qd = (uint64_t)g.n_q_heads * g.head_dim,
+                 kd = (uint64_t)g.n_kv_heads * g.head_dim, V = g.vocab;
+  WeightSet ws;
+  ws.has_bias = w->bq != nullptr;
+  uint64_t cursor = 0;
+  hipError_t herr = hipSuccess;
+  auto get = [&](const void* p, uint64_t n) -> const bf16* {
+    if (w->dtype == AREAL_DTYPE_BF16) return reinterpret_cast<const bf16*>(p);
+    bf16* dst = c->wsp<bf16>(c->lay.wconv) + cursor;
+    cursor += align_up(n, 64);
+    if (herr == hipSuccess) herr = launch_f32_to_bf16(c->stream, reinterpret_cast<const float*>(p), dst, (int64_t)n);
+    return dst;
+  };
+  const bool tied = w->lm_head == w->embed;
+  ws.embed = get(w->embed, V * H);
+  ws.lm_head = tied ? ws.embed : get(w->lm_head, V * H);
+  ws.final_norm = get(w->final_norm, H);
+  for (int l = 0; l < L; ++l) {
+    ws.wq.push_back(get(w->wq[l], qd * H));
+    ws.wk.push_back(get(w->wk[l], kd * H));
+    ws.wv.push_back(get(w->wv[l], kd * H));
+    ws.wo.push_back(get(w->wo[l], H * qd));
+    ws.wgate.push_back(get(w->wgate[l], F * H));
+    ws.wup.push_back(get(w->wup[l], F * H));
+    ws.wdown.push_back(get(w->wdown[l], H * F));
+    ws.norm_attn.push_back(get(w->norm_attn[l], H));
+    ws.norm_ffn.push_back(get(w->norm_ffn[l], H));
+    if (ws.has_bias) {
+      ws.bq.push_back(get(w->bq[l], qd));
+      ws.bk.push_back(get(w->bk[l], kd));
+      ws.bv.push_back(get(w->bv[l], kd));
+    }
+  }
+  if (herr != hipSuccess) return fail(c, AREAL_E_HIP, std::string("weight conversion: ") + hipGetErrorString(herr));
+  c->w = std::move(ws);
+  c->have_weights = true;
+  return AREAL_OK;
+}
+
+int check_weights_arg(areal_ctx* c, const areal_weights* w) {
+  if (!weights_complete(c, w)) return fail(c, AREAL_E_INVAL, "incomplete weight set");
+  if (w->dtype != AREAL_DTYPE_BF16 && w->dtype != AREAL_DTYPE_F32) return fail(c, AREAL_E_INVAL, "unknown weight dtype");
+  if (w->dtype == AREAL_DTYPE_F32 && !c->cfg.fp32_weights)
+    return fail(c, AREAL_E_INVAL, "float32 weights need cfg.fp32_weights = 1 at creation");
+  return AREAL_OK;
+}
+
+// ---- one forward pass -------------------------------------------------------
+struct PassArgs {
+  int M;                          // rows
+  RowMeta rm;                     // device
+  const int32_t* tokens_in;       // device or null (read history)
+  const int32_t* new_block;       // device or null
+  bool decode;
+  int chunk, n_splits;            // decode attention partition
+  const AttnWork* work;           // prefill attention work list (device)
+  int n_work;
+  const int32_t* last_rows;       // device: rows feeding the output projection (null: all rows)
+  int n_out;                      // logits rows produced
+  float* logits;                  // device [n_out, vocab]
+};
+
+int run_pass(areal_ctx* c, const PassArgs& a) {
+  const areal_model_cfg& g = c->cfg;
+  const int H = g.hidden, F = g.ffn, nq = g.n_q_heads, nkv = g.n_kv_heads, d = g.head_dim;
+  const int qd = nq * d, kd = nkv * d;
+  hipStream_t s = c->stream;
+  SeqState st = c->seq_state();
+  float* h = c->wsp<float>(c->lay.h);
+  bf16* xn = c->wsp<bf16>(c->lay.xn);
+  float* qkv = c->wsp<float>(c->lay.qkv);
+  bf16* q = c->wsp<bf16>(c->lay.q);
+  bf16* attn = c->wsp<bf16>(c->lay.attn);
+  bf16* act = c->wsp<bf16>(c->lay.act);
+  bf16* xlast = c->wsp<bf16>(c->lay.xlast);
+  const float* cos_t = c->wsp<float>(c->lay.cos_t);
+  const float* sin_t = c->wsp<float>(c->lay.sin_t);
+  bf16* arena = reinterpret_cast<bf16*>(g.kv_arena);
+  const WeightSet& w = c->w;
+
+  HIP_TRY(c, launch_embed(s, w.embed, H, g.vocab, a.M, a.rm, a.tokens_in, a.new_block, st, h));
+  for (int l = 0; l < g.n_layers; ++l) {
+    bf16* arena_l = arena + (int64_t)l * c->geom.layer_stride;
+    HIP_TRY(c, launch_rmsnorm(s, h, w.norm_attn[l], xn, a.M, H, g.rms_eps, nullptr));
+    GemmW wqkv{{w.wq[l], w.wk[l], w.wv[l]}, {qd, qd + kd, qd + 2 * kd}};
+    HIP_TRY(c, launch_gemm(s, xn, wqkv, qkv, a.M, qd + 2 * kd, H, qd + 2 * kd, GEMM_STORE_F32));
+    HIP_TRY(c, launch_rope_kvwrite(s, qkv, a.M, a.rm, st, w.has_bias ? w.bq[l] : nullptr,
+                                   w.has_bias ? w.bk[l] : nullptr, w.has_bias ? w.bv[l] : nullptr, cos_t,
+                                   sin_t, q, arena_l, c->geom, nq));
+    if (a.decode)
+      HIP_TRY(c, launch_attn_decode(s, q, a.M, a.rm, st, arena_l, c->geom, nq, a.chunk, a.n_splits,
+                                    c->wsp<float>(c->lay.part_o), c->wsp<float>(c->lay.part_ml), attn));
+    else
+      HIP_TRY(c, launch_attn_prefill(s, q, a.work, a.n_work, st, arena_l, c->geom, nq, attn));
+    GemmW wo{{w.wo[l], nullptr, nullptr}, {H, 0, 0}};
+    HIP_TRY(c, launch_gemm(s, attn, wo, h, a.M, H, qd, H, GEMM_ADD_F32));
+    HIP_TRY(c, launch_rmsnorm(s, h, w.norm_ffn[l], xn, a.M, H, g.rms_eps, nullptr));
+    GemmW wgu{{w.wgate[l], w.wup[l], nullptr}, {F, 0, 0}};
+    HIP_TRY(c, launch_gemm(s, xn, wgu, act, a.M, F, H, F, GEMM_SWIGLU_BF16));
+    GemmW wd{{w.wdown[l], nullptr, nullptr}, {H, 0, 0}};
+    HIP_TRY(c, launch_gemm(s, act, wd, h, a.M, H, F, H, GEMM_ADD_F32));
+  }
+  if (a.n_out > 0) {
+    HIP_TRY(c, launch_rmsnorm(s, h, w.final_norm, xlast, a.n_out, H, g.rms_eps, a.last_rows));
+    GemmW wl{{w.lm_head, nullptr, nullptr}, {g.vocab, 0, 0}};
+    HIP_TRY(c, launch_gemm(s, xlast, wl, a.logits, a.n_out, g.vocab, H, g.vocab, GEMM_STORE_F32));
+  }
+  return AREAL_OK;
+}
+
+// Prefill-style passes over `spans` (prompt tokens given, or history re-read when
+// tokens == null).  install_blocks: rows at block starts install their block id.
+int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* tokens,
+              const std::vector<int64_t>& tok_offset, bool install_blocks, float* logits_out) {
+  const areal_model_cfg& g = c->cfg;
+  auto passes = plan_passes(spans, g.max_batch_tokens);
+  // span index lookup for token offsets: pieces come in span order
+  size_t span_i = 0;
+  int done_in_span = 0;
+  for (auto& pass : passes) {
+    int M = 0, n_work = 0, n_out = 0;
+    for (auto& p : pass) {
+      M += p.len;
+      n_work += (p.len + 63) / 64;
+      if (p.out_index >= 0) ++n_out;
+    }
+    const uint64_t bytes = align_up((uint64_t)M * 4, 64) * 4 + align_up((uint64_t)n_work * sizeof(AttnWork), 64) +
+                           align_up((uint64_t)std::max(n_out, 1) * 4, 64);
+    int rc = ring_begin(c, bytes);
+    if (rc) return rc;
+    const uint64_t start = c->seg_used;
+    Staged s_slot = ring_take(c, (uint64_t)M * 4), s_pos = ring_take(c, (uint64_t)M * 4);
+    Staged s_tok = ring_take(c, (uint64_t)M * 4), s_nb = ring_take(c, (uint64_t)M * 4);
+    Staged s_work = ring_take(c, (uint64_t)n_work * sizeof(AttnWork));
+    Staged s_last = ring_take(c, (uint64_t)std::max(n_out, 1) * 4);
+    int32_t *hslot = (int32_t*)s_slot.host, *hpos = (int32_t*)s_pos.host, *htok = (int32_t*)s_tok.host,
+            *hnb = (int32_t*)s_nb.host, *hlast = (int32_t*)s_last.host;
+    AttnWork* hwork = (AttnWork*)s_work.host;
+    int wi = 0, oi = 0, first_out = -1;
+    for (auto& p : pass) {
+      const auto& blocks = c->alloc->blocks(p.slot);
+      for (int r = 0; r < p.len; ++r) {
+        const int pos = p.pos0 + r;
+        hslot[p.row0 + r] = p.slot;
+        hpos[p.row0 + r] = pos;
+        if (tokens) htok[p.row0 + r] = tokens[tok_offset[span_i] + done_in_span + r];
+        hnb[p.row0 + r] = (install_blocks && pos % AREAL_KV_BLOCK_TOKENS == 0) ? blocks[pos / AREAL_KV_BLOCK_TOKENS] : -1;
+      }
+      for (int r = 0; r < p.len; r += 64) hwork[wi++] = AttnWork{p.slot, p.row0 + r, p.pos0 + r, std::min(64, p.len - r)};
+      done_in_span += p.len;
+      if (p.out_index >= 0) {
+        if (first_out < 0) first_out = p.out_index;
+        hlast[oi++] = p.row0 + p.len - 1;
+        ++span_i;
+        done_in_span = 0;
+      }
+    }
+    rc = ring_flush(c, start);
+    if (rc) return rc;
+    PassArgs a{};
+    a.M = M;
+    a.rm = RowMeta{(const int32_t*)s_slot.dev, (const int32_t*)s_pos.dev};
+    a.tokens_in = tokens ? (const int32_t*)s_tok.dev : nullptr;
+    a.new_block = install_blocks ? (const int32_t*)s_nb.dev : nullptr;
+    a.decode = false;
+    a.work = (const AttnWork*)s_work.dev;
+    a.n_work = n_work;
+    a.last_rows = (const int32_t*)s_last.dev;
+    a.n_out = n_out;
+    a.logits = n_out > 0 ? logits_out + (int64_t)first_out * g.vocab : nullptr;
+    rc = run_pass(c, a);
+    if (rc) return rc;
+  }
+  return AREAL_OK;
+}
+
+}  // namespace
+
+// ============================================================== C boundary ===
+extern "C" {
+
+uint64_t areal_workspace_bytes(const areal_model_cfg* cfg) {
+  if (!cfg_valid(cfg, nullptr)) return 0;
+  return make_layout(*cfg).total;
+}
+
+uint64_t areal_kv_block_bytes(const areal_model_cfg* cfg) {
+  if (!cfg_valid(cfg, nullptr)) return 0;
+  return (uint64_t)cfg->n_layers * cfg->n_kv_heads * 2 * AREAL_KV_BLOCK_TOKENS * cfg->head_dim * 2;
+}
+
+const char* areal_last_error(const areal_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+int areal_create(const areal_model_cfg* cfg, areal_ctx** out) {
+  std::string why;
+  if (!out) return fail(nullptr, AREAL_E_INVAL, "out is NULL");
+  *out = nullptr;
+  if (!cfg_valid(cfg, &why)) return fail(nullptr, AREAL_E_INVAL, why);
+  Layout lay = make_layout(*cfg);
+  if (!cfg->workspace || ((uintptr_t)cfg->workspace & 255) || cfg->workspace_bytes < lay.total)
+    return fail(nullptr, AREAL_E_NOMEM, "workspace missing, misaligned or smaller than areal_workspace_bytes");
+  const uint64_t blk = areal_kv_block_bytes(cfg);
+  if (!cfg->kv_arena || ((uintptr_t)cfg->kv_arena & 255) || cfg->kv_arena_bytes < blk)
+    return fail(nullptr, AREAL_E_NOMEM, "kv_arena missing, misaligned or smaller than one block");
+  areal_ctx* c = new areal_ctx();
+  c->cfg = *cfg;
+  c->lay = lay;
+  c->stream = reinterpret_cast<hipStream_t>(cfg->hip_stream);
+  c->ws = reinterpret_cast<char*>(cfg->workspace);
+  c->n_blocks = (int64_t)std::min<uint64_t>(cfg->kv_arena_bytes / blk, 0x7fffffff);
+  c->geom.n_kv_heads = cfg->n_kv_heads;
+  c->geom.head_dim = cfg->head_dim;
+  c->geom.block_stride = cfg->n_kv_heads * 2 * AREAL_KV_BLOCK_TOKENS * cfg->head_dim;
+  c->geom.layer_stride = c->n_blocks * (int64_t)c->geom.block_stride;
+  c->alloc = new KvAllocator(c->n_blocks, cfg->max_seqs, lay.max_blocks, AREAL_KV_BLOCK_TOKENS);
+  c->seqs.resize(cfg->max_seqs);
+  c->seg_bytes = lay.ring_bytes / kRingSegs;
+  for (int i = 0; i < kRingSegs; ++i) { c->seg_done[i] = nullptr; c->seg_recorded[i] = false; }
+  auto die = [&](hipError_t e, const char* what) {
+    std::string m = std::string(what) + ": " + hipGetErrorString(e);
+    areal_destroy(c);
+    return fail(nullptr, AREAL_E_HIP, m);
+  };
+  hipError_t e = hipHostMalloc((void**)&c->ring_host, lay.ring_bytes, hipHostMallocDefault);
+  if (e != hipSuccess) { c->ring_host = nullptr; return die(e, "hipHostMalloc(ring)"); }
+  for (int i = 0; i < kRingSegs; ++i) {
+    e = hipEventCreateWithFlags(&c->seg_done[i], hipEventDisableTiming);
+    if (e != hipSuccess) { c->seg_done[i] = nullptr; return die(e, "hipEventCreate"); }
+  }
+  // rotary tables: angle = pos * theta^(-2j/d), evaluated in double
+  {
+    const int half = cfg->head_dim / 2;
+    std::vector<float> ct((size_t)cfg->max_seq_len * half), sn(ct.size());
+    std::vector<double> freq(half);
+    for (int j = 0; j < half; ++j) freq[j] = pow((double)cfg->rope_theta, -2.0 * j / cfg->head_dim);
+    for (int p = 0; p < cfg->max_seq_len; ++p)
+      for (int j = 0; j < half; ++j) {
+        const double a = (double)p * freq[j];
+        ct[(size_t)p * half + j] = (float)cos(a);
+        sn[(size_t)p * half + j] = (float)sin(a);
+      }
+    e = hipMemcpyAsync(c->ws + lay.cos_t, ct.data(), ct.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(c->ws + lay.sin_t, sn.data(), sn.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return die(e, "rotary table upload");
+  }
+  *out = c;
+  return AREAL_OK;
+}
+
+int areal_destroy(areal_ctx* c) {
+  if (!c) return AREAL_E_INVAL;
+  (void)hipStreamSynchronize(c->stream);
+  for (int i = 0; i < kRingSegs; ++i)
+    if (c->seg_done[i]) (void)hipEventDestroy(c->seg_done[i]);
+  if (c->ring_host) (void)hipHostFree(c->ring_host);
+  delete c->alloc;
+  delete c;
+  return AREAL_OK;
+}
+
+int areal_load_weights(areal_ctx* c, const areal_weights* w, uint64_t version) {
+  if (!c) return AREAL_E_INVAL;
+  int rc = check_weights_arg(c, w);
+  if (rc) return rc;
+  for (auto& s : c->seqs)
+    if (s.live) return fail(c, AREAL_E_STATE, "sequences are live: use areal_update_weights_interrupt");
+  if (version > (uint64_t)INT64_MAX) return fail(c, AREAL_E_INVAL, "version too large");
+  rc = install_weights(c, w);
+  if (rc) return rc;
+  c->version = (int64_t)version;
+  return AREAL_OK;
+}
+
+int areal_prefill(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t* tokens,
+                  const int32_t* cu, float* logits_out) {
+  if (!c) return AREAL_E_INVAL;
+  if (!c->have_weights) return fail(c, AREAL_E_STATE, "no weights loaded");
+  if (n <= 0 || !seq_ids || !tokens || !cu || !logits_out) return fail(c, AREAL_E_INVAL, "NULL or empty argument");
+  const areal_model_cfg& g = c->cfg;
+  if (cu[0] != 0) return fail(c, AREAL_E_INVAL, "cu_seqlens[0] must be 0");
+  std::vector<char> seen(g.max_seqs, 0);
+  int64_t need_blocks = 0;
+  for (int i = 0; i < n; ++i) {
+    const int id = seq_ids[i];
+    if (id < 0 || id >= g.max_seqs || seen[id]) return fail(c, AREAL_E_INVAL, "sequence id out of range or repeated");
+    if (c->seqs[id].live) return fail(c, AREAL_E_INVAL, "sequence id already live");
+    seen[id] = 1;
+    const int64_t len = (int64_t)cu[i + 1] - cu[i];
+    if (len < 1) return fail(c, AREAL_E_INVAL, "every prompt needs at least one token");
+    if (len > g.max_seq_len) return fail(c, AREAL_E_NOMEM, "prompt longer than max_seq_len");
+    need_blocks += c->alloc->blocks_for(len);
+  }
+  for (int64_t t = 0; t < cu[n]; ++t)
+    if (tokens[t] < 0 || tokens[t] >= g.vocab) return fail(c, AREAL_E_INVAL, "token id outside the vocabulary");
+  if (need_blocks > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
+  std::vector<Span> spans;
+  std::vector<int64_t> tok_off;
+  for (int i = 0; i < n; ++i) {
+    const int id = seq_ids[i], len = cu[i + 1] - cu[i];
+    c->alloc->reserve(id, len);
+    SeqInfo& s = c->seqs[id];
+    s.live = true;
+    s.len = len;
+    s.pending_version = c->version;
+    s.versions.assign(len, -1);
+    spans.push_back(Span{id, 0, len, i});
+    tok_off.push_back(cu[i]);
+  }
+  return run_spans(c, spans, tokens, tok_off, true, logits_out);
+}
+
+int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t* tokens_in,
+                      float* logits_out) {
+  if (!c) return AREAL_E_INVAL;
+  if (!c->have_weights) return fail(c, AREAL_E_STATE, "no weights loaded");
+  if (n <= 0 || !seq_ids || !tokens_in || !logits_out) return fail(c, AREAL_E_INVAL, "NULL or empty argument");
+  const areal_model_cfg& g = c->cfg;
+  if (n > g.max_seqs) return fail(c, AREAL_E_INVAL, "more rows than max_seqs");
+  std::vector<char> seen(g.max_seqs, 0);
+  int64_t need_blocks = 0;
+  for (int i = 0; i < n; ++i) {
+    const int id = seq_ids[i];
+    if (id < 0 || id >= g.max_seqs || seen[id]) return fail(c, AREAL_E_INVAL, "sequence id out of range or repeated");
+    if (!c->seqs[id].live) return fail(c, AREAL_E_STATE, "decode on a sequence that was not prefilled");
+    seen[id] = 1;
+    if (c->seqs[id].len + 1 > g.max_seq_len) return fail(c, AREAL_E_NOMEM, "sequence would exceed max_seq_len");
+    need_blocks += c->alloc->extra_needed(id, c->seqs[id].len + 1);
+  }
+  if (need_blocks > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
+  int rc = ring_begin(c, align_up((uint64_t)n * 4, 64) * 3);
+  if (rc) return rc;
+  const uint64_t start = c->seg_used;
+  Staged s_slot = ring_take(c, (uint64_t)n * 4), s_pos = ring_take(c, (uint64_t)n * 4),
+         s_nb = ring_take(c, (uint64_t)n * 4);
+  int32_t *hslot = (int32_t*)s_slot.host, *hpos = (int32_t*)s_pos.host, *hnb = (int32_t*)s_nb.host;
+  int64_t sum_ctx = 0;
+  int max_ctx = 0;
+  for (int i = 0; i < n; ++i) {
+    const int id = seq_ids[i];
+    SeqInfo& s = c->seqs[id];
+    const int pos = s.len;
+    const size_t had = c->alloc->blocks(id).size();
+    c->alloc->reserve(id, pos + 1);
+    hslot[i] = id;
+    hpos[i] = pos;
+    hnb[i] = c->alloc->blocks(id).size() > had ? c->alloc->blocks(id).back() : -1;
+    s.versions.push_back(s.pending_version);
+    s.len = pos + 1;
+    s.pending_version = c->version;
+    sum_ctx += pos + 1;
+    max_ctx = std::max(max_ctx, pos + 1);
+  }
+  rc = ring_flush(c, start);
+  if (rc) return rc;
+  // split the KV walk so that the grid holds a few work-groups per compute unit
+  int64_t chunk = (sum_ctx * g.n_kv_heads / 2048 + 127) / 128 * 128;
+  chunk = std::max<int64_t>(chunk, 256);
+  int n_splits = (int)((max_ctx + chunk - 1) / chunk);
+  if (n_splits > kMaxSplits) {
+    chunk = ((max_ctx + kMaxSplits - 1) / kMaxSplits + 127) / 128 * 128;
+    n_splits = (int)((max_ctx + chunk - 1) / chunk);
+  }
+  PassArgs a{};
+  a.M = n;
+  a.rm = RowMeta{(const int32_t*)s_slot.dev, (const int32_t*)s_pos.dev};
+  a.tokens_in = tokens_in;
+  a.new_block = (const int32_t*)s_nb.dev;
+  a.decode = true;
+  a.chunk = (int)chunk;
+  a.n_splits = n_splits;
+  a.last_rows = nullptr;
+  a.n_out = n;
+  a.logits = logits_out;
+  return run_pass(c, a);
+}
+
+int areal_sample_logprob(areal_ctx* c, int32_t n, const float* logits, const int32_t* seq_ids,
+                         const int32_t* positions, float temperature, float top_p, uint64_t seed,
+                         const int32_t* forced, int32_t* tokens_out, float* logp_behav, float* logp_full) {
+  if (!c) return AREAL_E_INVAL;
+  if (n <= 0 || !logits || !tokens_out || !logp_behav) return fail(c, AREAL_E_INVAL, "NULL or empty argument");
+  if (!(temperature > 0.f) || !(top_p > 0.f)) return fail(c, AREAL_E_INVAL, "temperature and top_p must be > 0");
+  if (!forced && (!seq_ids || !positions)) return fail(c, AREAL_E_INVAL, "seq_ids and positions are required to draw");
+  const int32_t *d_ids = nullptr, *d_pos = nullptr;
+  if (!forced) {
+    int rc = ring_begin(c, align_up((uint64_t)n * 4, 64) * 2);
+    if (rc) return rc;
+    const uint64_t start = c->seg_used;
+    Staged a = ring_take(c, (uint64_t)n * 4), b = ring_take(c, (uint64_t)n * 4);
+    memcpy(a.host, seq_ids, (size_t)n * 4);
+    memcpy(b.host, positions, (size_t)n * 4);
+    rc = ring_flush(c, start);
+    if (rc) return rc;
+    d_ids = (const int32_t*)a.dev;
+    d_pos = (const int32_t*)b.dev;
+  }
+  const float inv_t = 1.0f / temperature;
+  HIP_TRY(c, launch_sampler(c->stream, n, c->cfg.vocab, logits, d_ids, d_pos, inv_t, top_p, seed, forced,
+                            tokens_out, logp_behav, logp_full));
+  return AREAL_OK;
+}
+
+int areal_update_weights_interrupt(areal_ctx* c, const areal_weights* new_w, uint64_t new_version,
+                                   int32_t* n_live_out, int32_t* live_ids_out, float* logits_out,
+                                   int64_t* retok_out) {
+  if (!c) return AREAL_E_INVAL;
+  if (!c->have_weights) return fail(c, AREAL_E_STATE, "no weights loaded");
+  int rc = check_weights_arg(c, new_w);
+  if (rc) return rc;
+  if (!n_live_out || !live_ids_out) return fail(c, AREAL_E_INVAL, "NULL output argument");
+  if (new_version > (uint64_t)INT64_MAX || (int64_t)new_version <= c->version)
+    return fail(c, AREAL_E_STATE, "new_version must be greater than the current version");
+  std::vector<Span> spans;
+  int64_t total = 0;
+  int nl = 0;
+  for (int id = 0; id < c->cfg.max_seqs; ++id)
+    if (c->seqs[id].live) {
+      spans.push_back(Span{id, 0, c->seqs[id].len, nl});
+      total += c->seqs[id].len;
+      ++nl;
+    }
+  if (nl > 0 && !logits_out) return fail(c, AREAL_E_INVAL, "logits_out is NULL with live sequences");
+  rc = install_weights(c, new_w);       // stream-ordered after every earlier pass
+  if (rc) return rc;
+  c->version = (int64_t)new_version;
+  *n_live_out = nl;
+  for (int i = 0; i < nl; ++i) {
+    live_ids_out[i] = spans[i].slot;
+    c->seqs[spans[i].slot].pending_version = c->version;
+  }
+  if (retok_out) *retok_out = total;
+  if (nl == 0) return AREAL_OK;
+  // old K/V is never read again: every position is rewritten under the new
+  // weights, in position order, before any later position attends to it
+  return run_spans(c, spans, nullptr, {}, false, logits_out);
+}
+
+int areal_free_seq(areal_ctx* c, int32_t id) {
+  if (!c) return AREAL_E_INVAL;
+  if (id < 0 || id >= c->cfg.max_seqs || !c->seqs[id].live) return fail(c, AREAL_E_INVAL, "sequence not live");
+  c->alloc->release(id);
+  c->seqs[id] = SeqInfo();
+  return AREAL_OK;
+}
+
+int areal_seq_len(areal_ctx* c, int32_t id, int32_t* len_out) {
+  if (!c || !len_out) return AREAL_E_INVAL;
+  if (id < 0 || id >= c->cfg.max_seqs) return fail(c, AREAL_E_INVAL, "sequence id out of range");
+  *len_out = c->seqs[id].live ? c->seqs[id].len : -1;
+  return AREAL_OK;
+}
+
+int areal_get_tokens(areal_ctx* c, int32_t id, int32_t* out) {
+  if (!c || !out) return AREAL_E_INVAL;
+  if (id < 0 || id >= c->cfg.max_seqs || !c->seqs[id].live) return fail(c, AREAL_E_INVAL, "sequence not live");
+  HIP_TRY(c, hipMemcpyAsync(out, c->wsp<int32_t>(c->lay.hist) + (int64_t)id * c->cfg.max_seq_len,
+                            (size_t)c->seqs[id].len * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return AREAL_OK;
+}
+
+int areal_get_versions(areal_ctx* c, int32_t id, int64_t* out) {
+  if (!c || !out) return AREAL_E_INVAL;
+  if (id < 0 || id >= c->cfg.max_seqs || !c->seqs[id].live) return fail(c, AREAL_E_INVAL, "sequence not live");
+  memcpy(out, c->seqs[id].versions.data(), c->seqs[id].versions.size() * sizeof(int64_t));
+  return AREAL_OK;
+}
+
+int areal_kv_blocks(areal_ctx* c, int64_t* total, int64_t* free_) {
+  if (!c) return AREAL_E_INVAL;
+  if (total) *total = c->alloc->n_blocks();
+  if (free_) *free_ = c->alloc->n_free();
+  return AREAL_OK;
+}
+
+int areal_adopt_seq(areal_ctx* c, int32_t id, int32_t len, int32_t fill_token) {
+  if (!c) return AREAL_E_INVAL;
+  const areal_model_cfg& g = c->cfg;
+  if (id < 0 || id >= g.max_seqs || c->seqs[id].live) return fail(c, AREAL_E_INVAL, "sequence id out of range or live");
+  if (len < 1 || len > g.max_seq_len) return fail(c, AREAL_E_INVAL, "bad length");
+  if (fill_token < 0 || fill_token >= g.vocab) return fail(c, AREAL_E_INVAL, "token id outside the vocabulary");
+  if (c->alloc->extra_needed(id, len) > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
+  const uint64_t nb = c->alloc->blocks_for(len);
+  int rc = ring_begin(c, align_up(nb * 4, 64));
+  if (rc) return rc;
+  c->alloc->reserve(id, len);
+  Staged t = ring_take(c, nb * 4);
+  memcpy(t.host, c->alloc->blocks(id).data(), nb * 4);
+  HIP_TRY(c, hipMemcpyAsync(c->wsp<int32_t>(c->lay.table) + (int64_t)id * c->lay.max_blocks, t.host, nb * 4,
+                            hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipMemsetD32Async((hipDeviceptr_t)(c->wsp<int32_t>(c->lay.hist) + (int64_t)id * g.max_seq_len),
+                               fill_token, (size_t)len, c->stream));
+  SeqInfo& s = c->seqs[id];
+  s.live = true;
+  s.len = len;
+  s.pending_version = c->version;
+  s.versions.assign(len, -1);
+  return AREAL_OK;
+}
+
+// ---- host-only test surface (include/areal_host.h) ---------------------------
+struct areal_kvalloc { KvAllocator a; };
+
+areal_kvalloc* areal_kvalloc_create(int64_t n_blocks, int32_t max_seqs, int32_t max_blocks_per_seq) {
+  if (n_blocks < 0 || max_seqs <= 0 || max_blocks_per_seq <= 0) return nullptr;
+  return new areal_kvalloc{KvAllocator(n_blocks, max_seqs, max_blocks_per_seq, AREAL_KV_BLOCK_TOKENS)};
+}
+void areal_kvalloc_destroy(areal_kvalloc* a) { delete a; }
+int areal_kvalloc_reserve(areal_kvalloc* a, int32_t seq, int64_t n_tokens) { return a->a.reserve(seq, n_tokens) ? 0 : AREAL_E_NOMEM; }
+void areal_kvalloc_release(areal_kvalloc* a, int32_t seq) { a->a.release(seq); }
+int64_t areal_kvalloc_free_blocks(const areal_kvalloc* a) { return a->a.n_free(); }
+int32_t areal_kvalloc_table(const areal_kvalloc* a, int32_t seq, int32_t* out, int32_t cap) {
+  const auto& b = a->a.blocks(seq);
+  for (size_t i = 0; i < b.size() && (int)i < cap; ++i) out[i] = b[i];
+  return (int32_t)b.size();
+}
+void areal_kvalloc_shuffle(areal_kvalloc* a, uint64_t seed) { a->a.shuffle_free(seed); }
+
+int32_t areal_plan_passes(int32_t n_spans, const int32_t* lens, int32_t max_rows, int32_t* out, int32_t cap) {
+  std::vector<Span> spans;
+  for (int i = 0; i < n_spans; ++i) spans.push_back(Span{i, 0, lens[i], i});
+  auto passes = plan_passes(spans, max_rows);
+  int n = 0;
+  for (size_t p = 0; p < passes.size(); ++p)
+    for (auto& pc : passes[p]) {
+      if (n < cap) {
+        int32_t* o = out + (int64_t)n * 6;
+        o[0] = (int32_t)p; o[1] = pc.slot; o[2] = pc.pos0; o[3] = pc.len; o[4] = pc.row0; o[5] = pc.out_index;
+      }
+      ++n;
+    }
+  return n;
+}
+
+}  // extern "C"

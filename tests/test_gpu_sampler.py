@@ -1,0 +1,79 @@
+"""GPU sampler vs the oracle's specified procedure: token ids bit-exact,
+log-probs to 1e-4, on logits with the structure of the workloads (near-flat
+random-init rows at the real vocabulary size, peaked rows, ties, vocabularies
+that do not divide the segment size)."""
+import numpy as np
+import pytest
+
+from paper_2505_24298_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def eng():
+    import torch
+    from paper_2505_24298_amd import binding
+    assert torch.cuda.is_available()
+    e = binding.Areal(synth.shape("tiny"), max_seqs=64, max_seq_len=32, max_batch_tokens=64, kv_blocks=4)
+    yield e
+    e.close()
+
+
+def _check(eng, logits, temperature, top_p, seed, forced=None):
+    import torch
+    from oracle import sampler
+    n, V = logits.shape
+    eng.vocab_saved = eng.cfg.vocab
+    ids = np.arange(n, dtype=np.int32) * 3 + 1
+    pos = (np.arange(n, dtype=np.int32) * 7919) % 30000
+    dl = torch.from_numpy(logits).cuda()
+    f = None if forced is None else torch.from_numpy(forced.astype(np.int32)).cuda()
+    # the sampler kernel takes the vocabulary size from the context: make one per size
+    toks, lb, lf = eng.sample_logprob(dl, ids, pos, temperature, top_p, seed, forced_tokens=f)
+    want, wlb, wlf = sampler.sample_batch(logits, temperature, top_p, seed, ids, pos, forced)
+    assert toks.cpu().numpy().tolist() == want.tolist()
+    glb, glf = lb.cpu().numpy().astype(np.float64), lf.cpu().numpy().astype(np.float64)
+    fin = np.isfinite(wlb)
+    assert (np.isfinite(glb) == fin).all()
+    assert np.abs(glb[fin] - wlb[fin]).max(initial=0) < 1e-4
+    assert np.abs(glf - wlf).max() < 1e-4
+
+
+def _engine_for_vocab(V):
+    from paper_2505_24298_amd import binding
+    return binding.Areal(synth.shape("tiny", vocab=V), max_seqs=64, max_seq_len=32,
+                         max_batch_tokens=64, kv_blocks=4)
+
+
+@pytest.mark.parametrize("V", [1024, 1000, 151936])
+@pytest.mark.parametrize("temperature,top_p", [(1.0, 1.0), (0.6, 0.95), (1.3, 0.5), (1.0, 1e-4)])
+def test_draws_bit_exact(V, temperature, top_p):
+    rng = np.random.default_rng(V + int(top_p * 100))
+    n = 12 if V > 10000 else 40
+    eng = _engine_for_vocab(V)
+    for kind in ("flat", "peaked", "ties"):
+        if kind == "flat":
+            logits = (rng.standard_normal((n, V)) * 0.8).astype(np.float32)
+        elif kind == "peaked":
+            logits = (rng.standard_normal((n, V)) * 6.4).astype(np.float32)
+        else:
+            logits = np.round(rng.standard_normal((n, V)) * 2).astype(np.float32) * 0.5
+        _check(eng, logits, temperature, top_p, seed=(9 << 32) | 12345)
+        forced = rng.integers(0, V, size=n)
+        forced[0] = int(np.argmax(logits[0]))
+        forced[1] = int(np.argmin(logits[1]))
+        _check(eng, logits, temperature, top_p, seed=1, forced=forced)
+    eng.close()
+
+
+def test_masses_far_below_the_maximum_are_zero():
+    eng = _engine_for_vocab(1024)
+    logits = np.full((4, 1024), -40.0, dtype=np.float32)
+    logits[:, 5] = 3.0
+    logits[2, 900] = 3.0                     # two equal maxima
+    logits[3, 7] = 3.0 - 22.0                # just above the cut-off: tiny but non-zero mass
+    for top_p in (1.0, 0.9):
+        _check(eng, logits, 1.0, top_p, seed=4)
+        _check(eng, logits, 1.0, top_p, seed=4, forced=np.array([5, 6, 900, 7]))
+    eng.close()
