@@ -127,7 +127,7 @@ def test_tiny_interrupt_matches_fresh_prefill_under_new_weights(torch, binding):
 
 def test_top_p_temperature_teacher_forced(torch, binding):
     cfg = synth.shape("tiny")
-    w = synth.make_weights(cfg, 8, std=0.08)
+    w = synth.make_weights(cfg, 8)
     prompts = synth.make_prompts(cfg, 3, 2, 8, 24, seed=7)
     dl, dlb, dlf = _teacher_forced_run(torch, binding, cfg, w, prompts, 24, temperature=0.6, top_p=0.95,
                                        seed=(5 << 32) | 77)

@@ -10,26 +10,14 @@ from paper_2505_24298_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def eng():
-    import torch
-    from paper_2505_24298_amd import binding
-    assert torch.cuda.is_available()
-    e = binding.Areal(synth.shape("tiny"), max_seqs=64, max_seq_len=32, max_batch_tokens=64, kv_blocks=4)
-    yield e
-    e.close()
-
-
 def _check(eng, logits, temperature, top_p, seed, forced=None):
     import torch
     from oracle import sampler
     n, V = logits.shape
-    eng.vocab_saved = eng.cfg.vocab
     ids = np.arange(n, dtype=np.int32) * 3 + 1
     pos = (np.arange(n, dtype=np.int32) * 7919) % 30000
     dl = torch.from_numpy(logits).cuda()
     f = None if forced is None else torch.from_numpy(forced.astype(np.int32)).cuda()
-    # the sampler kernel takes the vocabulary size from the context: make one per size
     toks, lb, lf = eng.sample_logprob(dl, ids, pos, temperature, top_p, seed, forced_tokens=f)
     want, wlb, wlf = sampler.sample_batch(logits, temperature, top_p, seed, ids, pos, forced)
     assert toks.cpu().numpy().tolist() == want.tolist()
@@ -41,6 +29,7 @@ def _check(eng, logits, temperature, top_p, seed, forced=None):
 
 
 def _engine_for_vocab(V):
+    # the sampler takes the vocabulary size from the context: one context per size
     from paper_2505_24298_amd import binding
     return binding.Areal(synth.shape("tiny", vocab=V), max_seqs=64, max_seq_len=32,
                          max_batch_tokens=64, kv_blocks=4)
