@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the rollout hot path on one MI355X.
+
+One "step" = one whole rollout of the named workload: prefill of every
+prompt, then sample + decode until every sequence has produced its pre-drawn
+number of tokens (weights and prompts resident in HBM before the clock
+starts).  With --interrupt-every N the in-flight weight update of the paper's
+interruptible rollout fires every N decode steps (new weights prepared
+beforehand), as in the interrupt workload.
+
+Prints ONE JSON line: generated tokens/s for the whole job, the roofline of the
+dominant kernel (paged decode attention, HBM-bound) measured with HIP events
+inside the timed region, and the CPU oracle timed on the host cores as a
+baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16
+
+
+def device_weights(torch, cfg, seed, device, base=None, scale=None):
+    """Random-init bf16 parameter set on the device: matrices and embeddings
+    N(0, 0.02), gains 1.  With `base`: base + scale * N(0,1) (the interrupt
+    workload's perturbed weights)."""
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+
+    def mat(shape, old=None):
+        x = torch.randn(shape, generator=g, device=device, dtype=torch.float32)
+        if old is None:
+            x.mul_(0.02)
+        else:
+            x.mul_(scale).add_(old.float())
+        return x.to(torch.bfloat16).contiguous()
+
+    H, F, V = cfg["hidden"], cfg["ffn"], cfg["vocab"]
+    qd, kd = cfg["n_q_heads"] * cfg["head_dim"], cfg["n_kv_heads"] * cfg["head_dim"]
+    shapes = dict(wq=(qd, H), wk=(kd, H), wv=(kd, H), wo=(H, qd), wgate=(F, H), wup=(F, H), wdown=(H, F))
+    ones = lambda: torch.ones(H, device=device, dtype=torch.bfloat16)
+    w = dict(embed=mat((V, H), None if base is None else base["embed"]), layers=[])
+    for l in range(cfg["n_layers"]):
+        lw = {k: mat(s, None if base is None else base["layers"][l][k]) for k, s in shapes.items()}
+        lw["norm_attn"], lw["norm_ffn"] = ones(), ones()
+        w["layers"].append(lw)
+    w["final_norm"] = ones()
+    w["lm_head"] = mat((V, H), None if base is None else base["lm_head"])
+    return w
+
+
+def decode_step_bytes(cfg, ctx_sum, n):
+    """Algorithmic HBM bytes of one decode step over n sequences whose contexts
+    sum to ctx_sum tokens: every weight once, every cached K/V once, the new K/V
+    rows, the logits written once and read once by the sampler."""
+    H, F, V, L = cfg["hidden"], cfg["ffn"], cfg["vocab"], cfg["n_layers"]
+    qd, kd = cfg["n_q_heads"] * cfg["head_dim"], cfg["n_kv_heads"] * cfg["head_dim"]
+    w_elems = L * (qd * H + 2 * kd * H + H * qd + 3 * F * H + 2 * H) + H + V * H
+    kv_token = L * 2 * kd * 2
+    return 2 * w_elems + kv_token * ctx_sum + kv_token * n + 2 * 4 * n * V
+
+
+def prefill_flops(cfg, lens):
+    H, F, V, L = cfg["hidden"], cfg["ffn"], cfg["vocab"], cfg["n_layers"]
+    qd, kd = cfg["n_q_heads"] * cfg["head_dim"], cfg["n_kv_heads"] * cfg["head_dim"]
+    p_layers = L * (qd * H + 2 * kd * H + H * qd + 3 * F * H)
+    lens = np.asarray(lens, dtype=np.float64)
+    return float(2 * p_layers * lens.sum() + 2 * V * H * len(lens)
+                 + 4 * qd * L * (lens * (lens + 1) / 2).sum())
+
+
+def rollout(eng, torch, cfg, prompts, out_lens, temperature, top_p, seed, interrupt_every=0,
+            weight_sets=None, profile=None):
+    """Run one whole rollout.  Sequences are ordered by output length
+    (longest first) so the live set is always a prefix of the batch.  Returns
+    timings and counters."""
+    order = np.argsort(-np.asarray(out_lens), kind="stable")
+    prompts = [prompts[i] for i in order]
+    out_lens = np.asarray(out_lens)[order]
+    n = len(prompts)
+    ids = np.arange(n, dtype=np.int32)
+    plen = np.array([len(p) for p in prompts])
+    dev = eng.device
+    logits = torch.empty((n, cfg["vocab"]), dtype=torch.float32, device=dev)
+    logits_b = torch.empty_like(logits) if interrupt_every else None
+    toks = torch.empty(n, dtype=torch.int32, device=dev)
+    lb = torch.empty(n, dtype=torch.float32, device=dev)
+    lf = torch.empty(n, dtype=torch.float32, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    e_start, e_prefill, e_end = ev(), ev(), ev()
+    res = dict(prefill_tokens=int(plen.sum()), gen_tokens=int(out_lens.sum()), decode_steps=0,
+               decode_bytes=0.0, reprefill_tokens=0, interrupts=0, reprefill_ms=0.0)
+    re_events = []
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e_start.record()
+    eng.prefill(ids, prompts, logits_out=logits)
+    e_prefill.record()
+    if profile is not None:
+        eng.profile_begin(profile[0], profile[1], profile[2])
+    gen = 0                                     # tokens generated so far per live sequence
+    live = n
+    max_new = int(out_lens.max())
+    version = 0
+    while True:
+        # sample token number gen+1 for every live sequence
+        eng.sample_logprob(logits[:live], ids[:live], plen[:live] + gen, temperature, top_p, seed,
+                           out=(toks[:live], lb[:live], lf[:live]))
+        gen += 1
+        # sequences whose output is complete leave (they sit at the tail of the order)
+        new_live = int(np.searchsorted(-out_lens, -gen, side="left"))      # out_lens > gen
+        for s in range(new_live, live):
+            eng.free_seq(s)
+        live = new_live
+        if live == 0:
+            break
+        if interrupt_every and gen % interrupt_every == 0:
+            # in-flight weight update: the token just sampled is appended first (its
+            # logits came from the old version), then every prefix is recomputed
+            a, b = ev(), ev()
+            eng.decode_step(ids[:live], toks[:live], logits_out=logits[:live])
+            res["decode_bytes"] += decode_step_bytes(cfg, int((plen[:live] + gen).sum()), live)
+            res["decode_steps"] += 1
+            version += 1
+            a.record()
+            _, _, retok = eng.update_weights_interrupt(weight_sets[version % len(weight_sets)], version,
+                                                       logits_out=logits_b)
+            b.record()
+            re_events.append((a, b))
+            logits, logits_b = logits_b, logits
+            res["reprefill_tokens"] += retok
+            res["interrupts"] += 1
+            continue
+        eng.decode_step(ids[:live], toks[:live], logits_out=logits[:live])
+        res["decode_bytes"] += decode_step_bytes(cfg, int((plen[:live] + gen).sum()), live)
+        res["decode_steps"] += 1
+    e_end.record()
+    torch.cuda.synchronize()
+    res["wall_s"] = time.perf_counter() - t0
+    if profile is not None:
+        res["profile"] = eng.profile_end()
+    res["total_ms"] = e_start.elapsed_time(e_end)
+    res["prefill_ms"] = e_start.elapsed_time(e_prefill)
+    res["reprefill_ms"] = float(sum(a.elapsed_time(b) for a, b in re_events))
+    res["decode_ms"] = res["total_ms"] - res["prefill_ms"] - res["reprefill_ms"]
+    res["prefill_flops"] = prefill_flops(cfg, plen)
+    res["max_new"] = max_new
+    return res
+
+
+def cpu_oracle_baseline(cfg_name, budget_s=20.0):
+    """The CPU oracle as it stands (incremental-KV variant, numpy float64) on a
+    bounded slice of the same workload: 2 sequences of the workload's model
+    shape, prompts cut to 32 tokens, a few decode steps, stopping near the time
+    budget.  Returns generated tokens/s over that slice."""
+    import threadpoolctl
+    from oracle import rollout as orollout
+    from paper_2505_24298_amd import synth
+    cfg = synth.shape(cfg_name)
+    t_w = time.perf_counter()
+    w = synth.make_weights(cfg, 0, round_bf16=True)
+    t_w = time.perf_counter() - t_w
+    prompts = synth.make_prompts(cfg, 2, 1, 32, 32, seed=1)
+    wk = orollout.RolloutWorker(cfg, w, version=0, seed=0, use_cache=True)
+    t0 = time.perf_counter()
+    for s, p in enumerate(prompts):
+        wk.add(s, p)
+    t_prefill = time.perf_counter() - t0
+    steps = 0
+    t1 = time.perf_counter()
+    while time.perf_counter() - t0 < budget_s or steps < 2:
+        wk.step([0, 1])
+        steps += 1
+        if steps >= 64:
+            break
+    t_dec = time.perf_counter() - t1
+    threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+    return dict(value=round(2 * steps / t_dec, 3), unit="gen tokens/s", cores=int(threads), kind="oracle",
+                sample=f"{cfg_name} shape, 2 sequences x 32-token prompts, {steps} decode steps "
+                       f"(incremental-KV float64 numpy oracle; prefill of the 64 prompt tokens took "
+                       f"{t_prefill:.1f} s and is not in the rate)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=0)
+    ap.add_argument("--workload", default="qwen2-1.5b-rollout")
+    ap.add_argument("--scale-out", type=float, default=1.0, help="scale every output length (quick runs)")
+    ap.add_argument("--interrupt-every", type=int, default=0)
+    ap.add_argument("--max-batch-tokens", type=int, default=8192)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-class", type=int, default=4, help="kernel class bracketed with events")
+    ap.add_argument("--profile-every", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one MI355X: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_24298_amd import binding, synth
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = "cuda:0"
+    cfg, wl, prompts, out_lens = synth.make_workload(args.workload, scale_out=args.scale_out)
+    n = len(prompts)
+    max_len = int(max(len(p) + o for p, o in zip(prompts, out_lens))) + 1
+    # KV pool: what the workload can hold at its peak, plus slack
+    peak_tokens = int(sum(len(p) + o for p, o in zip(prompts, out_lens)))
+    kv_blocks = peak_tokens // 16 + 2 * n + 64
+    eng = binding.Areal(cfg, max_seqs=n, max_seq_len=max_len, max_batch_tokens=args.max_batch_tokens,
+                        kv_blocks=kv_blocks)
+    w0 = device_weights(torch, cfg, 0, dev)
+    weight_sets = [w0]
+    if args.interrupt_every:
+        weight_sets.append(device_weights(torch, cfg, 1001, dev, base=w0, scale=1e-3))
+    # priming run (untimed, not a warmup step): 2 sequences, 3 tokens: loads the code objects
+    eng.load_weights(w0, 0)
+    rollout(eng, torch, cfg, prompts[:2], [3, 3], wl["temperature"], wl["top_p"], 0)
+
+    runs = []
+    for it in range(args.warmup + args.steps):
+        eng.load_weights(w0, 0)
+        prof = (args.profile_class, 0, args.profile_every)
+        r = rollout(eng, torch, cfg, prompts, out_lens, wl["temperature"], wl["top_p"], 0,
+                    interrupt_every=args.interrupt_every, weight_sets=weight_sets, profile=prof)
+        if it >= args.warmup:
+            runs.append(r)
+    total_s = sum(r["total_ms"] for r in runs) / 1e3
+    gen = sum(r["gen_tokens"] for r in runs)
+    dec_ms = sum(r["decode_ms"] for r in runs)
+    pre_ms = sum(r["prefill_ms"] for r in runs)
+    dec_bytes = sum(r["decode_bytes"] for r in runs)
+    pn, pms, punits = (sum(r["profile"][i] for r in runs) for i in range(3))
+    kv_layer_bytes = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * 2          # K+V bytes per token per layer
+    if args.profile_class == binding.K_ATTN_DECODE and pn:
+        achieved = punits * kv_layer_bytes / (pms * 1e-3) / 1e9
+        roofline = dict(bound="hbm", kernel="attn_decode_kernel", achieved=round(achieved, 1),
+                        peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
+                        traffic=None, launches_timed=int(pn), avg_launch_us=round(pms / pn * 1e3, 2),
+                        avg_context_tokens_per_launch=round(punits / pn, 1))
+    else:
+        roofline = dict(bound="hbm", kernel=f"class {args.profile_class}", achieved=None, peak=HBM_PEAK_GBS,
+                        unit="GB/s", frac=None, traffic=None, launches_timed=int(pn),
+                        avg_launch_us=round(pms / max(pn, 1) * 1e3, 2))
+    out = {
+        "metric": "gen tokens/s, 1 MI355X, Qwen2-1.5B shape; decode HBM GB/s % of peak",
+        "value": round(gen / total_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(total_s * 1e3 / args.steps, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload + (f" x{args.scale_out} output length" if args.scale_out != 1 else "")
+                   + (f", weight update every {args.interrupt_every} decode steps" if args.interrupt_every else ""),
+                   "sequences": n, "prompt_tokens": runs[0]["prefill_tokens"],
+                   "generated_tokens": runs[0]["gen_tokens"], "decode_steps": runs[0]["decode_steps"],
+                   "sampling": f"T={wl['temperature']} top_p={wl['top_p']}"},
+        "decode": {"tokens_per_s": round(gen / (dec_ms * 1e-3), 1),
+                   "hbm_GBps_algorithmic": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
+                   "hbm_frac_of_peak": round(dec_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                   "ms_per_decode_step": round(dec_ms / max(1, sum(r["decode_steps"] for r in runs)), 4)},
+        "prefill": {"tokens_per_s": round(sum(r["prefill_tokens"] for r in runs) / (pre_ms * 1e-3), 1),
+                    "mfma_frac_of_peak": round(sum(r["prefill_flops"] for r in runs) / (pre_ms * 1e-3)
+                                               / (MFMA_BF16_PEAK_TFLOPS * 1e12), 4)},
+        "roofline": roofline,
+    }
+    if args.interrupt_every:
+        rt, rms = sum(r["reprefill_tokens"] for r in runs), sum(r["reprefill_ms"] for r in runs)
+        out["interrupt"] = {"count": runs[0]["interrupts"], "reprefill_tokens_per_s": round(rt / (rms * 1e-3), 1),
+                            "reprefill_ms_total": round(rms, 1),
+                            "reprefill_over_decode_time": round(rms / dec_ms, 4)}
+    eng.close()
+    del eng
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_oracle_baseline(wl["shape"])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -184,6 +184,30 @@ int areal_kv_blocks(areal_ctx* ctx, int64_t* total_out, int64_t* free_out);
  * timed at a chosen context depth without generating up to it. */
 int areal_adopt_seq(areal_ctx* ctx, int32_t seq_id, int32_t len, int32_t fill_token);
 
+/* Measurement hook (Section 3.2 motivates the roofline: decoding is memory-IO
+ * bound).  Between areal_profile_begin and areal_profile_end the library
+ * brackets one kernel launch of class `kernel_class` (layer `layer` of every
+ * `every`-th forward pass; the sampler and the output projection have no
+ * layer) with HIP events on the stream.  areal_profile_end waits for the
+ * stream and reports how many launches were bracketed, their summed duration,
+ * and their summed work units: context tokens read (attention decode),
+ * query-key pairs (attention prefill), rows (everything else). */
+#define AREAL_K_EMBED 0
+#define AREAL_K_RMSNORM 1
+#define AREAL_K_GEMM_QKV 2
+#define AREAL_K_ROPE_KVWRITE 3
+#define AREAL_K_ATTN_DECODE 4
+#define AREAL_K_ATTN_PREFILL 5
+#define AREAL_K_GEMM_O 6
+#define AREAL_K_GEMM_GATEUP 7
+#define AREAL_K_GEMM_DOWN 8
+#define AREAL_K_GEMM_LMHEAD 9
+#define AREAL_K_SAMPLER 10
+#define AREAL_K_COUNT 11
+int areal_profile_begin(areal_ctx* ctx, int32_t kernel_class, int32_t layer, int32_t every);
+int areal_profile_end(areal_ctx* ctx, int64_t* n_samples_out, double* total_ms_out,
+                      double* total_units_out);
+
 #ifdef __cplusplus
 }
 #endif

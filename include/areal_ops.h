@@ -1,0 +1,33 @@
+/*
+ * areal_ops.h -- single-kernel entry points of the library, for parity tests
+ * and tuning sweeps of one kernel in isolation.  They launch exactly the
+ * kernels the generation calls of areal.h launch; all pointers are device
+ * pointers, the work is enqueued on `hip_stream` and not waited for.
+ */
+#ifndef AREAL_OPS_H
+#define AREAL_OPS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* The projection GEMM of the decoder blocks (the dense contractions of the
+ * policy forward pass, Section 2 "LLM Training and Inference"):
+ *   mode 0: C float32 [M,N]  = A W0^T
+ *   mode 1: C float32 [M,N] += A W0^T
+ *   mode 2: C bf16    [M,N]  = silu(A W0^T) * (A W1^T)      (W0 gate, W1 up)
+ * A bf16 [M,K], W0/W1 bf16 [N,K], row-major, 16-byte aligned, K % 8 == 0.
+ * cfg = tile configuration 0 .. areal_op_gemm_num_configs()-1, or -1 for the
+ * library's own choice; splits = K split (>1 accumulates with float32 atomics:
+ * in mode 0 C must be zero beforehand), or -1 for the library's choice.
+ * Returns 0 or AREAL_E_INVAL / AREAL_E_HIP. */
+int areal_op_gemm(void* hip_stream, const void* A, const void* W0, const void* W1, void* C,
+                  int32_t M, int32_t N, int32_t K, int32_t mode, int32_t cfg, int32_t splits);
+int areal_op_gemm_num_configs(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AREAL_OPS_H */

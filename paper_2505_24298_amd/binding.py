@@ -17,6 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libareal.so")
 OK, E_INVAL, E_NOMEM, E_STATE, E_HIP = 0, -1, -2, -3, -4
 DTYPE_F32, DTYPE_BF16 = 0, 1
 KV_BLOCK_TOKENS = 16
+(K_EMBED, K_RMSNORM, K_GEMM_QKV, K_ROPE_KVWRITE, K_ATTN_DECODE, K_ATTN_PREFILL, K_GEMM_O,
+ K_GEMM_GATEUP, K_GEMM_DOWN, K_GEMM_LMHEAD, K_SAMPLER) = range(11)
 
 
 class ArealError(RuntimeError):
@@ -70,6 +72,12 @@ _SIGNATURES = {
     "areal_get_versions": (C.c_int, [C.c_void_p, C.c_int32, _I64P]),
     "areal_kv_blocks": (C.c_int, [C.c_void_p, _I64P, _I64P]),
     "areal_adopt_seq": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
+    "areal_profile_begin": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
+    "areal_profile_end": (C.c_int, [C.c_void_p, _I64P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    # include/areal_ops.h
+    "areal_op_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "areal_op_gemm_num_configs": (C.c_int, []),
     # include/areal_host.h
     "areal_kvalloc_create": (C.c_void_p, [C.c_int64, C.c_int32, C.c_int32]),
     "areal_kvalloc_destroy": (None, [C.c_void_p]),
@@ -276,10 +284,29 @@ class Areal:
         self._check(self.L.areal_get_versions(self.ctx, int(seq_id), out.ctypes.data_as(_I64P)))
         return out
 
+    def profile_begin(self, kernel_class, layer=0, every=1):
+        self._check(self.L.areal_profile_begin(self.ctx, int(kernel_class), int(layer), int(every)))
+
+    def profile_end(self):
+        n, ms, units = C.c_int64(), C.c_double(), C.c_double()
+        self._check(self.L.areal_profile_end(self.ctx, C.byref(n), C.byref(ms), C.byref(units)))
+        return n.value, ms.value, units.value
+
     def kv_blocks(self):
         t, f = C.c_int64(), C.c_int64()
         self._check(self.L.areal_kv_blocks(self.ctx, C.byref(t), C.byref(f)))
         return t.value, f.value
+
+
+def op_gemm(A, W0, W1, C_out, mode, cfg=-1, splits=-1):
+    """areal_op_gemm on torch tensors (current stream)."""
+    import torch
+    M, K = A.shape
+    N = W0.shape[0]
+    rc = lib().areal_op_gemm(torch.cuda.current_stream().cuda_stream, A.data_ptr(), W0.data_ptr(),
+                             None if W1 is None else W1.data_ptr(), C_out.data_ptr(), M, N, K, mode, cfg, splits)
+    if rc != OK:
+        raise ArealError(rc, "areal_op_gemm")
 
 
 def weights_to_device(w, device="cuda:0", bf16=True):

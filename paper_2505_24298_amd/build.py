@@ -44,6 +44,8 @@ def build(verbose=True):
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    import ctypes
+    ctypes.CDLL(LIB)            # fails here, at build time, on an unresolved symbol
     if verbose:
         print(f"built {LIB}")
     return LIB

@@ -49,7 +49,8 @@ hipError_t launch_embed(hipStream_t s, const bf16* embed, int hidden, int vocab,
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x,
                                                       const bf16* __restrict__ gain,
                                                       bf16* __restrict__ y, int M, int H, float eps,
-                                                      const int32_t* __restrict__ src_rows) {
+                                                      const int32_t* __restrict__ src_rows,
+                                                      float* __restrict__ zero_out, int zero_cols) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= M) return;
@@ -71,12 +72,17 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
     for (int i = 0; i < 4; ++i) o[i] = f2bf(v[i] * r * bf2f(g[i]));
     *reinterpret_cast<bf16x4*>(yp + c) = o;
   }
+  if (zero_out) {
+    float* zp = zero_out + (int64_t)row * zero_cols;
+    const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
+    for (int c = lane * 4; c < zero_cols; c += 256) *reinterpret_cast<f32x4*>(zp + c) = z4;
+  }
 }
 
 hipError_t launch_rmsnorm(hipStream_t s, const float* x, const bf16* gain, bf16* y, int M, int hidden,
-                          float eps, const int32_t* src_rows) {
-  if (M <= 0 || hidden % 4) return hipErrorInvalidValue;
-  rmsnorm_kernel<<<(M + 3) / 4, 256, 0, s>>>(x, gain, y, M, hidden, eps, src_rows);
+                          float eps, const int32_t* src_rows, float* zero_out, int zero_cols) {
+  if (M <= 0 || hidden % 4 || (zero_out && zero_cols % 4)) return hipErrorInvalidValue;
+  rmsnorm_kernel<<<(M + 3) / 4, 256, 0, s>>>(x, gain, y, M, hidden, eps, src_rows, zero_out, zero_cols);
   return hipGetLastError();
 }
 

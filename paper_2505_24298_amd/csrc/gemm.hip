@@ -1,8 +1,13 @@
 // bf16 x bf16 -> float32 GEMM on the gfx950 matrix cores.
 //   C[M,N] (+)= A[M,K] * W[N,K]^T      (both operands K-contiguous)
 // Work-group tile BM x BN x 64 staged through LDS with register prefetch of
-// the next K-slab; four wavefronts in a 2 x 2 grid, each computing
-// (BM/2) x (BN/2) with v_mfma_f32_32x32x16_bf16.
+// the next K-slab; WM x WN wavefronts, each computing (BM/WM) x (BN/WN) with
+// v_mfma_f32_32x32x16_bf16.  The K range can be split over work-groups
+// (float32 atomic accumulation into C) so that skinny decode-shape products
+// still fill 256 compute units; the block id -> tile map keeps the row tiles
+// that share a weight panel on one XCD (one L2).
+#include <algorithm>
+
 #include "kernels.hpp"
 
 namespace areal {
@@ -17,10 +22,10 @@ constexpr int LDS_K = BK + 8;   // row stride in elements (144 B): conflict-free
 template <int BN, int MODE>
 __device__ __forceinline__ const bf16* w_row_ptr(const GemmW& W, int tile_n, int b, int N, int K) {
   if (MODE == GEMM_SWIGLU_BF16) {
-    // the wave column owns BN/2 tile rows: first half gate rows, second half up rows
-    const int wn = b / (BN / 2), rb = b % (BN / 2);
-    const int isup = rb / (BN / 4), c = rb % (BN / 4);
-    const int f = tile_n * (BN / 2) + wn * (BN / 4) + c;
+    // every 64 tile rows = 32 gate rows then 32 up rows of the same 32 features
+    const int grp = b >> 6, within = b & 63;
+    const int isup = within >> 5, c = within & 31;
+    const int f = tile_n * (BN / 2) + grp * 32 + c;
     return f < N ? W.ptr[isup] + (int64_t)f * K : nullptr;
   } else {
     const int n = tile_n * BN + b;
@@ -33,49 +38,77 @@ __device__ __forceinline__ const bf16* w_row_ptr(const GemmW& W, int tile_n, int
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
-template <int BM, int BN, int MODE>
-__global__ __launch_bounds__(256) void gemm_kernel(const bf16* __restrict__ A, GemmW W,
-                                                   void* __restrict__ Cv, int M, int N, int K,
-                                                   int ldc) {
-  constexpr int TM = BM / 64, TN = BN / 64;      // 32x32 MFMA tiles per wave
-  constexpr int ACH = BM / 32, BCH = BN / 32;    // 16-B chunks per thread per slab
+template <int BM, int BN, int WM, int WN, int MODE, bool RAGGED_K>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const bf16* __restrict__ A, GemmW W,
+                                                            void* __restrict__ Cv, int M, int N, int K,
+                                                            int ldc, int m_tiles, int n_tiles,
+                                                            int slabs_per_split, int atomic) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
+  constexpr int ACH = BM * 8 / NT, BCH = BN * 8 / NT;   // 16-B chunks per thread per slab
+  static_assert(TM >= 1 && TN >= 1 && ACH >= 1 && BCH >= 1, "tile too small for the wave grid");
+  static_assert(MODE != GEMM_SWIGLU_BF16 || (TN % 2 == 0), "SwiGLU needs gate+up in one wave tile");
   __shared__ __attribute__((aligned(16))) bf16 sA[2][BM * LDS_K];
   __shared__ __attribute__((aligned(16))) bf16 sB[2][BN * LDS_K];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int tile_n = blockIdx.x, m0 = blockIdx.y * BM;
-  const int kc = tid & 7, r0 = tid >> 3;         // chunk column, first chunk row
+  // block id -> (row tile, column tile, K split): ids that differ by a multiple
+  // of 8 sit on the same XCD; the row tiles of one weight panel are adjacent there.
+  const int id = blockIdx.x, xcd = id & 7, grp = id >> 3;
+  const int tile_m = grp % m_tiles;
+  const int rest = grp / m_tiles;
+  const int n_groups = (n_tiles + 7) >> 3;
+  const int tile_n = (rest % n_groups) * 8 + xcd;
+  const int split = rest / n_groups;
+  if (tile_n >= n_tiles) return;
 
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int m0 = tile_m * BM;
+  const int kc = tid & 7, r0 = tid >> 3;         // chunk column, first chunk row
+  constexpr int RSTEP = NT / 8;                  // rows covered per chunk round
+
+  // Rows outside the matrix are clamped to a valid row: they only feed
+  // accumulator rows / columns that are never stored.
   const bf16* pa[ACH];
   const bf16* pb[BCH];
 #pragma unroll
   for (int i = 0; i < ACH; ++i) {
-    const int m = m0 + r0 + 32 * i;
-    pa[i] = m < M ? A + (int64_t)m * K + kc * 8 : nullptr;
+    const int m = min(m0 + r0 + RSTEP * i, M - 1);
+    pa[i] = A + (int64_t)m * K + kc * 8;
   }
 #pragma unroll
   for (int i = 0; i < BCH; ++i) {
-    const bf16* p = w_row_ptr<BN, MODE>(W, tile_n, r0 + 32 * i, N, K);
-    pb[i] = p ? p + kc * 8 : nullptr;
+    const bf16* p = w_row_ptr<BN, MODE>(W, tile_n, r0 + RSTEP * i, N, K);
+    if (!p) p = w_row_ptr<BN, MODE>(W, 0, 0, N, K);
+    pb[i] = p + kc * 8;
   }
 
-  bf16x8 ra[ACH], rb[BCH];
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-  auto load_slab = [&](int k0) {
-    const bool kin = k0 + kc * 8 < K;            // K % 8 == 0: a chunk is all in or all out
+  struct Slab { bf16x8 a[ACH], b[BCH]; };
+  // RAGGED_K (K % 64 != 0; K % 8 == 0 always): a 16-byte chunk is all inside or
+  // all outside the row; outside chunks are fetched from the row start and zeroed.
+  auto load_slab = [&](Slab& r, int k0) {
+    if (RAGGED_K) {
+      const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+      const bool kin = k0 + kc * 8 < K;
+      const int ko = kin ? k0 : -kc * 8;
 #pragma unroll
-    for (int i = 0; i < ACH; ++i) ra[i] = (pa[i] && kin) ? ld8(pa[i] + k0) : zero8;
+      for (int i = 0; i < BCH; ++i) { const bf16x8 v = ld8(pb[i] + ko); r.b[i] = kin ? v : zero8; }
 #pragma unroll
-    for (int i = 0; i < BCH; ++i) rb[i] = (pb[i] && kin) ? ld8(pb[i] + k0) : zero8;
+      for (int i = 0; i < ACH; ++i) { const bf16x8 v = ld8(pa[i] + ko); r.a[i] = kin ? v : zero8; }
+    } else {
+#pragma unroll
+      for (int i = 0; i < BCH; ++i) r.b[i] = ld8(pb[i] + k0);
+#pragma unroll
+      for (int i = 0; i < ACH; ++i) r.a[i] = ld8(pa[i] + k0);
+    }
   };
-  auto store_slab = [&](int buf) {
+  auto store_slab = [&](const Slab& r, int buf) {
 #pragma unroll
     for (int i = 0; i < ACH; ++i)
-      *reinterpret_cast<bf16x8*>(&sA[buf][(r0 + 32 * i) * LDS_K + kc * 8]) = ra[i];
+      *reinterpret_cast<bf16x8*>(&sA[buf][(r0 + RSTEP * i) * LDS_K + kc * 8]) = r.a[i];
 #pragma unroll
     for (int i = 0; i < BCH; ++i)
-      *reinterpret_cast<bf16x8*>(&sB[buf][(r0 + 32 * i) * LDS_K + kc * 8]) = rb[i];
+      *reinterpret_cast<bf16x8*>(&sB[buf][(r0 + RSTEP * i) * LDS_K + kc * 8]) = r.b[i];
   };
 
   f32x16 acc[TM][TN];
@@ -86,32 +119,54 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16* __restrict__ A, G
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nk = (K + BK - 1) / BK;
-  load_slab(0);
-  store_slab(0);
-  __syncthreads();
   const int fr = lane & 31, fh = lane >> 5;      // fragment row, K half
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) load_slab((kt + 1) * BK);
+  auto compute = [&](int buf) {
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8 fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
         fa[i] = *reinterpret_cast<const bf16x8*>(
-            &sA[buf][(wm * (BM / 2) + i * 32 + fr) * LDS_K + kk * 16 + fh * 8]);
+            &sA[buf][(wm * (BM / WM) + i * 32 + fr) * LDS_K + kk * 16 + fh * 8]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
         fb[j] = *reinterpret_cast<const bf16x8*>(
-            &sB[buf][(wn * (BN / 2) + j * 32 + fr) * LDS_K + kk * 16 + fh * 8]);
+            &sB[buf][(wn * (BN / WN) + j * 32 + fr) * LDS_K + kk * 16 + fh * 8]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_slab(buf ^ 1);
+  };
+
+  // Software pipeline, two slabs of global loads in flight: while slab kt is
+  // multiplied out of LDS, slab kt+1 sits in one register set (already
+  // requested) and slab kt+2 is requested into the other.
+  const int nk_all = (K + BK - 1) / BK;
+  const int kt0 = split * slabs_per_split;
+  const int kt1 = min(nk_all, kt0 + slabs_per_split);
+  if (kt0 >= kt1) return;
+  Slab r0s, r1s;
+  // Loads are issued unconditionally (past the end they re-read the last slab)
+  // so that no branch separates a load from the wait that consumes it: the
+  // wait counters then let two slabs stay in flight.
+  const int k_last = (kt1 - 1) * BK;
+  load_slab(r0s, kt0 * BK);
+  load_slab(r1s, min((kt0 + 1) * BK, k_last));
+  store_slab(r0s, 0);
+  __syncthreads();
+  for (int kt = kt0; kt < kt1; kt += 2) {
+    // even step: LDS buffer 0 holds slab kt, r1s holds slab kt+1
+    load_slab(r0s, min((kt + 2) * BK, k_last));
+    compute(0);
+    store_slab(r1s, 1);
+    __syncthreads();
+    if (kt + 1 >= kt1) break;
+    // odd step: LDS buffer 1 holds slab kt+1, r0s holds slab kt+2
+    load_slab(r1s, min((kt + 3) * BK, k_last));
+    compute(1);
+    store_slab(r0s, 0);
     __syncthreads();
   }
 
@@ -121,13 +176,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16* __restrict__ A, G
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN / 2; ++j) {
-        const int f = tile_n * (BN / 2) + wn * (BN / 4) + j * 32 + fr;
+      for (int j = 0; j < TN; j += 2) {
+        // wave columns [wn*BN/WN + j*32, +64) = gate | up of 32 features
+        const int f = tile_n * (BN / 2) + (wn * (BN / WN) + j * 32) / 2 + fr;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int m = m0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+          const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
           if (m < M && f < N)
-            C[(int64_t)m * ldc + f] = f2bf(silu_f(acc[i][j][v]) * acc[i][j + TN / 2][v]);
+            C[(int64_t)m * ldc + f] = f2bf(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
         }
       }
   } else {
@@ -136,48 +192,342 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16* __restrict__ A, G
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = tile_n * BN + wn * (BN / 2) + j * 32 + fr;
+        const int n = tile_n * BN + wn * (BN / WN) + j * 32 + fr;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int m = m0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+          const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
           if (m < M && n < N) {
             float* p = C + (int64_t)m * ldc + n;
-            if (MODE == GEMM_ADD_F32) *p += acc[i][j][v]; else *p = acc[i][j][v];
+            if (atomic) unsafeAtomicAdd(p, acc[i][j][v]);
+            else if (MODE == GEMM_ADD_F32) *p += acc[i][j][v];
+            else *p = acc[i][j][v];
           }
         }
       }
   }
 }
 
-template <int BM, int BN, int MODE>
-hipError_t run(hipStream_t s, const bf16* A, const GemmW& W, void* C, int M, int N, int K, int ldc) {
-  const int n_out_per_tile = MODE == GEMM_SWIGLU_BF16 ? BN / 2 : BN;
-  dim3 grid((N + n_out_per_tile - 1) / n_out_per_tile, (M + BM - 1) / BM);
-  gemm_kernel<BM, BN, MODE><<<grid, 256, 0, s>>>(A, W, C, M, N, K, ldc);
+
+// ---- direct-to-LDS variant ---------------------------------------------------
+// Same tiling, but the K-slabs travel HBM -> LDS with global_load_lds_dwordx4
+// (no register staging) into a ring of STAGES slab buffers, so STAGES-1 slabs
+// of loads stay in flight per work-group.  One wavefront instruction moves a
+// group of 8 tile rows x 128 B; lane s of the group lands at byte s*16 of the
+// group's 1 KiB window, and fetches chunk (s&7) ^ (row&7) of row s>>3, an XOR
+// swizzle that makes the later 16-byte fragment reads bank-conflict free.
+// Requires K % 64 == 0.
+constexpr int GROUP_BYTES = 1024 + 128;   // 8 rows x 128 B, + 128 B skew between groups
+
+// 16 bytes per lane, HBM -> LDS: lane i of the wave writes dst_wave_base + i*16.
+__device__ __forceinline__ void dma16(const void* src, void* dst_wave_base) {
+  __builtin_amdgcn_global_load_lds(
+      (const __attribute__((address_space(1))) void*)src,
+      (__attribute__((address_space(3))) void*)dst_wave_base, 16, 0, 0);
+}
+
+__device__ __forceinline__ void wait_vmcnt(int n) {
+  // s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt = [15:14]:[3:0])
+  switch (n) {
+#define AREAL_W(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | 0x0F70); break;
+    AREAL_W(0) AREAL_W(1) AREAL_W(2) AREAL_W(3) AREAL_W(4) AREAL_W(5) AREAL_W(6) AREAL_W(7) AREAL_W(8)
+    AREAL_W(9) AREAL_W(10) AREAL_W(11) AREAL_W(12) AREAL_W(13) AREAL_W(14) AREAL_W(15) AREAL_W(16)
+    AREAL_W(18) AREAL_W(20) AREAL_W(21) AREAL_W(24) AREAL_W(27) AREAL_W(28) AREAL_W(30) AREAL_W(32)
+    AREAL_W(36) AREAL_W(40) AREAL_W(48)
+#undef AREAL_W
+    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, int MODE>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const bf16* __restrict__ A, GemmW W,
+                                                                void* __restrict__ Cv, int M, int N,
+                                                                int K, int ldc, int m_tiles,
+                                                                int n_tiles, int slabs_per_split,
+                                                                int atomic) {
+  constexpr int NW = WM * WN;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int GA = BM / 8, GB = BN / 8;              // row groups per slab
+  constexpr int LPS = (GA + GB) / NW;                  // load instructions per wave per slab
+  static_assert((GA + GB) % NW == 0 && GA % NW == 0, "row groups must divide over the waves");
+  static_assert(MODE != GEMM_SWIGLU_BF16 || (TN % 2 == 0), "SwiGLU needs gate+up in one wave tile");
+  constexpr int STAGE_BYTES = (GA + GB) * GROUP_BYTES;
+  __shared__ __attribute__((aligned(16))) char lds[STAGES * STAGE_BYTES];
+
+  const int id = blockIdx.x, xcd = id & 7, grp = id >> 3;
+  const int tile_m = grp % m_tiles;
+  const int rest = grp / m_tiles;
+  const int n_groups = (n_tiles + 7) >> 3;
+  const int tile_n = (rest % n_groups) * 8 + xcd;
+  const int split = rest / n_groups;
+  if (tile_n >= n_tiles) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int m0 = tile_m * BM;
+
+  // this wave's share of the row groups: GA/NW groups of A, then GB/NW of B
+  const bf16* src[LPS];
+  int dst_off[LPS];
+  {
+    const int rin = lane >> 3;                          // row inside the group
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) {
+      const bool is_a = i < GA / NW;
+      const int gi = is_a ? wave * (GA / NW) + i : wave * (GB / NW) + (i - GA / NW);
+      const int row = gi * 8 + rin;
+      const int chunk = (lane & 7) ^ (row & 7);
+      if (is_a) {
+        const int m = min(m0 + row, M - 1);
+        src[i] = A + (int64_t)m * K + chunk * 8;
+        dst_off[i] = gi * GROUP_BYTES;
+      } else {
+        const bf16* p = w_row_ptr<BN, MODE>(W, tile_n, row, N, K);
+        if (!p) p = w_row_ptr<BN, MODE>(W, 0, 0, N, K);
+        src[i] = p + chunk * 8;
+        dst_off[i] = (GA + gi) * GROUP_BYTES;
+      }
+    }
+  }
+  auto issue = [&](int stage, int k0) {
+#pragma unroll
+    for (int i = 0; i < LPS; ++i)
+      dma16(src[i] + k0, lds + stage * STAGE_BYTES + dst_off[i]);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int fr = lane & 31, fh = lane >> 5;
+  // fragment addressing: tile row R -> group R>>3, slot (R&7)*8 + (chunk ^ (R&7))
+  int a_base[TM], b_base[TN], koff[BK / 16];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int R = wm * (BM / WM) + i * 32 + fr;
+    a_base[i] = (R >> 3) * GROUP_BYTES + (R & 7) * 128;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int R = wn * (BN / WN) + j * 32 + fr;
+    b_base[j] = (GA + (R >> 3)) * GROUP_BYTES + (R & 7) * 128;
+  }
+#pragma unroll
+  for (int kk = 0; kk < BK / 16; ++kk) koff[kk] = ((kk * 2 + fh) ^ (fr & 7)) << 4;
+
+  auto compute = [&](int stage) {
+    const char* base = lds + stage * STAGE_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(base + a_base[i] + koff[kk]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(base + b_base[j] + koff[kk]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  const int nk_all = K / BK;
+  const int kt0 = split * slabs_per_split;
+  const int kt1 = min(nk_all, kt0 + slabs_per_split);
+  if (kt0 >= kt1) return;
+  const int k_last = (kt1 - 1) * BK;
+  // prologue: STAGES-1 slabs in flight (past the end: re-read the last slab, never consumed)
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s) issue(s, min((kt0 + s) * BK, k_last));
+  for (int kt = kt0; kt < kt1; kt += STAGES) {
+#pragma unroll
+    for (int u = 0; u < STAGES; ++u) {
+      if (kt + u < kt1) {
+        // slab kt+u sits in stage u; the STAGES-2 slabs requested after it may still be in flight
+        wait_vmcnt((STAGES - 2) * LPS);
+        // plain barrier (no fence: a fence would drain every outstanding load): every wave's
+        // part of slab kt+u has landed, and every wave has finished reading stage u-1
+        __builtin_amdgcn_s_barrier();
+        issue((u + STAGES - 1) % STAGES, min((kt + u + STAGES - 1) * BK, k_last));
+        compute(u);
+      }
+    }
+  }
+  // (all remaining in-flight loads target LDS only; the epilogue does not touch LDS)
+
+  if (MODE == GEMM_SWIGLU_BF16) {
+    bf16* C = reinterpret_cast<bf16*>(Cv);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; j += 2) {
+        const int f = tile_n * (BN / 2) + (wn * (BN / WN) + j * 32) / 2 + fr;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+          if (m < M && f < N)
+            C[(int64_t)m * ldc + f] = f2bf(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
+        }
+      }
+  } else {
+    float* C = reinterpret_cast<float*>(Cv);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = tile_n * BN + wn * (BN / WN) + j * 32 + fr;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+          if (m < M && n < N) {
+            float* p = C + (int64_t)m * ldc + n;
+            if (atomic) unsafeAtomicAdd(p, acc[i][j][v]);
+            else if (MODE == GEMM_ADD_F32) *p += acc[i][j][v];
+            else *p = acc[i][j][v];
+          }
+        }
+      }
+  }
+  // drain the loads that were requested past the end before the LDS is released
+  wait_vmcnt(0);
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, int MODE>
+hipError_t run_dma(hipStream_t s, const bf16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
+                   int splits) {
+  if (K % BK) return hipErrorInvalidValue;
+  constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_BF16 ? BN / 2 : BN;
+  const int n_tiles = (N + n_out_per_tile - 1) / n_out_per_tile, m_tiles = (M + BM - 1) / BM;
+  const int nk = K / BK;
+  splits = std::max(1, std::min(splits, nk));
+  const int sps = (nk + splits - 1) / splits;
+  splits = (nk + sps - 1) / sps;
+  const int n_groups = (n_tiles + 7) / 8;
+  const int grid = m_tiles * n_groups * 8 * splits;
+  gemm_dma_kernel<BM, BN, WM, WN, STAGES, MODE><<<grid, WM * WN * 64, 0, s>>>(
+      A, W, C, M, N, K, ldc, m_tiles, n_tiles, sps, splits > 1 ? 1 : 0);
   return hipGetLastError();
+}
+
+template <int BM, int BN, int WM, int WN, int MODE>
+hipError_t run(hipStream_t s, const bf16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
+               int splits) {
+  constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_BF16 ? BN / 2 : BN;
+  const int n_tiles = (N + n_out_per_tile - 1) / n_out_per_tile, m_tiles = (M + BM - 1) / BM;
+  const int nk = (K + BK - 1) / BK;
+  splits = std::max(1, std::min(splits, nk));
+  const int sps = (nk + splits - 1) / splits;
+  splits = (nk + sps - 1) / sps;
+  const int n_groups = (n_tiles + 7) / 8;
+  const int grid = m_tiles * n_groups * 8 * splits;
+  if (K % BK)
+    gemm_kernel<BM, BN, WM, WN, MODE, true><<<grid, WM * WN * 64, 0, s>>>(A, W, C, M, N, K, ldc, m_tiles,
+                                                                          n_tiles, sps, splits > 1 ? 1 : 0);
+  else
+    gemm_kernel<BM, BN, WM, WN, MODE, false><<<grid, WM * WN * 64, 0, s>>>(A, W, C, M, N, K, ldc, m_tiles,
+                                                                           n_tiles, sps, splits > 1 ? 1 : 0);
+  return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t dispatch(hipStream_t s, int cfg, const bf16* A, const GemmW& W, void* C, int M, int N, int K,
+                    int ldc, int splits) {
+  switch (cfg) {
+    case 0: return run<128, 128, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 1: return run<256, 128, 4, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 2: return run<64, 128, 1, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 3: return run<256, 64, 4, 1, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 4: return run<32, 128, 1, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 5: return run<128, 64, 2, 1, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 6: return run<64, 64, 1, 1, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    // direct-to-LDS ring (K % 64 == 0)
+    case 7: return run_dma<128, 128, 2, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 8: return run_dma<128, 128, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 9: return run_dma<256, 128, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 10: return run_dma<64, 128, 1, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 11: return run_dma<64, 128, 1, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 12: return run_dma<32, 128, 1, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 13: return run_dma<128, 64, 2, 1, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 14: return run_dma<256, 64, 4, 1, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 15: return run_dma<128, 128, 2, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
 
-hipError_t launch_gemm(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
-                       GemmMode mode) {
+int gemm_num_configs() { return 16; }
+
+// Tile configuration and K split for a product of this shape: rules read off
+// sweeps over every configuration on the MI355X at the decoder's shapes
+// (`cfg` / `splits` >= 0 in launch_gemm_cfg override them).
+void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
+  const bool dma_ok = (K % BK) == 0;
+  const int n_tiles = mode == GEMM_SWIGLU_BF16 ? (N + 63) / 64 : (N + 127) / 128;
+  const int nk = (K + BK - 1) / BK;
+  int c, bm;
+  if (!dma_ok) {                       // register-staged path (ragged K)
+    if (M <= 32) { c = 4; bm = 32; }
+    else if (M <= 64) { c = 2; bm = 64; }
+    else { c = 0; bm = 128; }
+  } else if (M > 256) {                // prefill: MFMA-bound, large tiles
+    c = 0; bm = 128;
+  } else if (n_tiles >= 100) {         // wide outputs: one work-group per column panel
+    if (M <= 32) { c = 12; bm = 32; }
+    else if (M <= 64) { c = 10; bm = 64; }
+    else if (M <= 128) { c = 7; bm = 128; }
+    else { c = 9; bm = 256; }
+  } else {                             // narrow outputs: small row tiles + K split
+    if (M <= 64 || K < 4096) { c = 12; bm = 32; }
+    else if (M <= 128) { c = 10; bm = 64; }
+    else { c = 7; bm = 128; }
+  }
+  int sp = 1;
+  if (mode != GEMM_SWIGLU_BF16 && M <= 256) {
+    const int tiles = n_tiles * ((M + bm - 1) / bm);
+    sp = (224 + tiles / 2) / std::max(tiles, 1);           // ~one work-group per compute unit
+    sp = std::max(1, std::min(sp, std::max(1, nk / 3)));   // at least 3 slabs per split
+  }
+  *cfg = c;
+  *splits = sp;
+}
+
+hipError_t launch_gemm_cfg(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
+                           GemmMode mode, int cfg, int splits) {
   if (M <= 0 || N <= 0 || K <= 0 || K % 8 || ldc < N || !A || !C || !W.ptr[0]) return hipErrorInvalidValue;
   if (((uintptr_t)A | (uintptr_t)W.ptr[0] | (uintptr_t)W.ptr[1] | (uintptr_t)W.ptr[2]) & 15)
     return hipErrorInvalidValue;
+  int c0, s0;
+  gemm_choose(M, N, K, mode, &c0, &s0);
+  if (cfg < 0) cfg = c0;
+  if (splits < 0) splits = s0;
   switch (mode) {
     case GEMM_STORE_F32:
       if (W.end[0] > N || (W.end[0] < N && (!W.ptr[1] || W.end[1] > N)) ||
           (W.end[0] < N && W.end[1] < N && (!W.ptr[2] || W.end[2] != N)))
         return hipErrorInvalidValue;
-      return run<128, 128, GEMM_STORE_F32>(s, A, W, C, M, N, K, ldc);
+      return dispatch<GEMM_STORE_F32>(s, cfg, A, W, C, M, N, K, ldc, splits);
     case GEMM_ADD_F32:
       if (W.end[0] != N) return hipErrorInvalidValue;
-      return run<128, 128, GEMM_ADD_F32>(s, A, W, C, M, N, K, ldc);
+      return dispatch<GEMM_ADD_F32>(s, cfg, A, W, C, M, N, K, ldc, splits);
     case GEMM_SWIGLU_BF16:
       if (!W.ptr[1]) return hipErrorInvalidValue;
-      return run<128, 128, GEMM_SWIGLU_BF16>(s, A, W, C, M, N, K, ldc);
+      return dispatch<GEMM_SWIGLU_BF16>(s, cfg, A, W, C, M, N, K, ldc, 1);
   }
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_gemm(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
+                       GemmMode mode) {
+  // GEMM_STORE_F32 callers that did not zero C get no K split
+  int cfg, splits;
+  gemm_choose(M, N, K, mode, &cfg, &splits);
+  if (mode == GEMM_STORE_F32) splits = 1;
+  return launch_gemm_cfg(s, A, W, C, M, N, K, ldc, mode, cfg, splits);
 }
 
 }  // namespace areal

@@ -20,8 +20,11 @@ struct SeqState {              // device-resident per-sequence state
 
 hipError_t launch_embed(hipStream_t s, const bf16* embed, int hidden, int vocab, int M, RowMeta rm,
                         const int32_t* tokens_in, const int32_t* new_block, SeqState st, float* h);
+// zero_out (optional): float32 [M, zero_cols] cleared row by row alongside (the
+// buffer a following split-K product accumulates into).
 hipError_t launch_rmsnorm(hipStream_t s, const float* x, const bf16* gain, bf16* y, int M, int hidden,
-                          float eps, const int32_t* src_rows);
+                          float eps, const int32_t* src_rows, float* zero_out = nullptr,
+                          int zero_cols = 0);
 hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
                                const bf16* bq, const bf16* bk, const bf16* bv, const float* cos_tab,
                                const float* sin_tab, bf16* q_out, bf16* arena_layer, KvGeom geom,
@@ -42,6 +45,13 @@ enum GemmMode {
 };
 hipError_t launch_gemm(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
                        GemmMode mode);
+// Same with an explicit tile configuration (0 .. gemm_num_configs()-1) and K
+// split; -1 = take the tuned choice.  A split > 1 accumulates with float32
+// atomics: for GEMM_STORE_F32 the caller must have zeroed C.
+hipError_t launch_gemm_cfg(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
+                           GemmMode mode, int cfg, int splits);
+void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits);
+int gemm_num_configs();
 
 // ---- attention.hip ----------------------------------------------------------
 struct AttnWork {              // prefill work item: 64 query rows of one sequence

@@ -11,6 +11,7 @@
 
 #include "../../include/areal.h"
 #include "../../include/areal_host.h"
+#include "../../include/areal_ops.h"
 #include "kernels.hpp"
 #include "kv_alloc.hpp"
 
@@ -120,6 +121,12 @@ struct areal_ctx {
   hipEvent_t seg_done[kRingSegs];
   bool seg_recorded[kRingSegs];
   std::string err;
+  // measurement hook
+  int prof_class = -1, prof_layer = 0, prof_every = 1;
+  int64_t prof_pass = 0;
+  double prof_units = 0.0;
+  std::vector<hipEvent_t> prof_events;      // start/stop pairs
+  size_t prof_used = 0;
 
   template <class T> T* wsp(uint64_t off) const { return reinterpret_cast<T*>(ws + off); }
   SeqState seq_state() const {
@@ -237,6 +244,29 @@ int check_weights_arg(areal_ctx* c, const areal_weights* w) {
   return AREAL_OK;
 }
 
+// ---- measurement hook ---------------------------------------------------------
+struct ProfScope {
+  areal_ctx* c;
+  bool on;
+  ProfScope(areal_ctx* c_, int klass, int layer, bool pass_sampled, double units) : c(c_), on(false) {
+    if (c->prof_class != klass || !pass_sampled || (layer >= 0 && layer != c->prof_layer)) return;
+    if (c->prof_used + 2 > c->prof_events.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) return;
+      if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+      c->prof_events.push_back(a);
+      c->prof_events.push_back(b);
+    }
+    on = hipEventRecord(c->prof_events[c->prof_used], c->stream) == hipSuccess;
+    if (on) c->prof_units += units;
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(c->prof_events[c->prof_used + 1], c->stream);
+    c->prof_used += 2;
+  }
+};
+
 // ---- one forward pass -------------------------------------------------------
 struct PassArgs {
   int M;                          // rows
@@ -250,6 +280,7 @@ struct PassArgs {
   const int32_t* last_rows;       // device: rows feeding the output projection (null: all rows)
   int n_out;                      // logits rows produced
   float* logits;                  // device [n_out, vocab]
+  double attn_units;              // context tokens read (decode) / query-key pairs (prefill)
 };
 
 int run_pass(areal_ctx* c, const PassArgs& a) {
@@ -270,30 +301,58 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
   bf16* arena = reinterpret_cast<bf16*>(g.kv_arena);
   const WeightSet& w = c->w;
 
-  HIP_TRY(c, launch_embed(s, w.embed, H, g.vocab, a.M, a.rm, a.tokens_in, a.new_block, st, h));
+  const bool sampled = c->prof_class >= 0 && (c->prof_pass++ % c->prof_every) == 0;
+  const double rows = a.M;
+  {
+    ProfScope ps(c, AREAL_K_EMBED, -1, sampled, rows);
+    HIP_TRY(c, launch_embed(s, w.embed, H, g.vocab, a.M, a.rm, a.tokens_in, a.new_block, st, h));
+  }
   for (int l = 0; l < g.n_layers; ++l) {
     bf16* arena_l = arena + (int64_t)l * c->geom.layer_stride;
-    HIP_TRY(c, launch_rmsnorm(s, h, w.norm_attn[l], xn, a.M, H, g.rms_eps, nullptr));
-    GemmW wqkv{{w.wq[l], w.wk[l], w.wv[l]}, {qd, qd + kd, qd + 2 * kd}};
-    HIP_TRY(c, launch_gemm(s, xn, wqkv, qkv, a.M, qd + 2 * kd, H, qd + 2 * kd, GEMM_STORE_F32));
-    HIP_TRY(c, launch_rope_kvwrite(s, qkv, a.M, a.rm, st, w.has_bias ? w.bq[l] : nullptr,
-                                   w.has_bias ? w.bk[l] : nullptr, w.has_bias ? w.bv[l] : nullptr, cos_t,
-                                   sin_t, q, arena_l, c->geom, nq));
-    if (a.decode)
+    {
+      ProfScope ps(c, AREAL_K_RMSNORM, l, sampled, rows);
+      // the QKV product may split K and accumulate atomically: clear its output here
+      HIP_TRY(c, launch_rmsnorm(s, h, w.norm_attn[l], xn, a.M, H, g.rms_eps, nullptr, qkv, qd + 2 * kd));
+    }
+    {
+      ProfScope ps(c, AREAL_K_GEMM_QKV, l, sampled, rows);
+      GemmW wqkv{{w.wq[l], w.wk[l], w.wv[l]}, {qd, qd + kd, qd + 2 * kd}};
+      HIP_TRY(c, launch_gemm_cfg(s, xn, wqkv, qkv, a.M, qd + 2 * kd, H, qd + 2 * kd, GEMM_STORE_F32, -1, -1));
+    }
+    {
+      ProfScope ps(c, AREAL_K_ROPE_KVWRITE, l, sampled, rows);
+      HIP_TRY(c, launch_rope_kvwrite(s, qkv, a.M, a.rm, st, w.has_bias ? w.bq[l] : nullptr,
+                                     w.has_bias ? w.bk[l] : nullptr, w.has_bias ? w.bv[l] : nullptr,
+                                     cos_t, sin_t, q, arena_l, c->geom, nq));
+    }
+    if (a.decode) {
+      ProfScope ps(c, AREAL_K_ATTN_DECODE, l, sampled, a.attn_units);
       HIP_TRY(c, launch_attn_decode(s, q, a.M, a.rm, st, arena_l, c->geom, nq, a.chunk, a.n_splits,
                                     c->wsp<float>(c->lay.part_o), c->wsp<float>(c->lay.part_ml), attn));
-    else
+    } else {
+      ProfScope ps(c, AREAL_K_ATTN_PREFILL, l, sampled, a.attn_units);
       HIP_TRY(c, launch_attn_prefill(s, q, a.work, a.n_work, st, arena_l, c->geom, nq, attn));
-    GemmW wo{{w.wo[l], nullptr, nullptr}, {H, 0, 0}};
-    HIP_TRY(c, launch_gemm(s, attn, wo, h, a.M, H, qd, H, GEMM_ADD_F32));
+    }
+    {
+      ProfScope ps(c, AREAL_K_GEMM_O, l, sampled, rows);
+      GemmW wo{{w.wo[l], nullptr, nullptr}, {H, 0, 0}};
+      HIP_TRY(c, launch_gemm_cfg(s, attn, wo, h, a.M, H, qd, H, GEMM_ADD_F32, -1, -1));
+    }
     HIP_TRY(c, launch_rmsnorm(s, h, w.norm_ffn[l], xn, a.M, H, g.rms_eps, nullptr));
-    GemmW wgu{{w.wgate[l], w.wup[l], nullptr}, {F, 0, 0}};
-    HIP_TRY(c, launch_gemm(s, xn, wgu, act, a.M, F, H, F, GEMM_SWIGLU_BF16));
-    GemmW wd{{w.wdown[l], nullptr, nullptr}, {H, 0, 0}};
-    HIP_TRY(c, launch_gemm(s, act, wd, h, a.M, H, F, H, GEMM_ADD_F32));
+    {
+      ProfScope ps(c, AREAL_K_GEMM_GATEUP, l, sampled, rows);
+      GemmW wgu{{w.wgate[l], w.wup[l], nullptr}, {F, 0, 0}};
+      HIP_TRY(c, launch_gemm_cfg(s, xn, wgu, act, a.M, F, H, F, GEMM_SWIGLU_BF16, -1, -1));
+    }
+    {
+      ProfScope ps(c, AREAL_K_GEMM_DOWN, l, sampled, rows);
+      GemmW wd{{w.wdown[l], nullptr, nullptr}, {H, 0, 0}};
+      HIP_TRY(c, launch_gemm_cfg(s, act, wd, h, a.M, H, F, H, GEMM_ADD_F32, -1, -1));
+    }
   }
   if (a.n_out > 0) {
     HIP_TRY(c, launch_rmsnorm(s, h, w.final_norm, xlast, a.n_out, H, g.rms_eps, a.last_rows));
+    ProfScope ps(c, AREAL_K_GEMM_LMHEAD, -1, sampled, (double)a.n_out);
     GemmW wl{{w.lm_head, nullptr, nullptr}, {g.vocab, 0, 0}};
     HIP_TRY(c, launch_gemm(s, xlast, wl, a.logits, a.n_out, g.vocab, H, g.vocab, GEMM_STORE_F32));
   }
@@ -329,7 +388,9 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
             *hnb = (int32_t*)s_nb.host, *hlast = (int32_t*)s_last.host;
     AttnWork* hwork = (AttnWork*)s_work.host;
     int wi = 0, oi = 0, first_out = -1;
+    double qk_pairs = 0.0;
     for (auto& p : pass) {
+      qk_pairs += (double)p.len * p.pos0 + 0.5 * (double)p.len * (p.len + 1);
       const auto& blocks = c->alloc->blocks(p.slot);
       for (int r = 0; r < p.len; ++r) {
         const int pos = p.pos0 + r;
@@ -360,6 +421,7 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
     a.last_rows = (const int32_t*)s_last.dev;
     a.n_out = n_out;
     a.logits = n_out > 0 ? logits_out + (int64_t)first_out * g.vocab : nullptr;
+    a.attn_units = qk_pairs;
     rc = run_pass(c, a);
     if (rc) return rc;
   }
@@ -446,6 +508,7 @@ int areal_destroy(areal_ctx* c) {
   for (int i = 0; i < kRingSegs; ++i)
     if (c->seg_done[i]) (void)hipEventDestroy(c->seg_done[i]);
   if (c->ring_host) (void)hipHostFree(c->ring_host);
+  for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
   delete c->alloc;
   delete c;
   return AREAL_OK;
@@ -564,6 +627,7 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
   a.last_rows = nullptr;
   a.n_out = n;
   a.logits = logits_out;
+  a.attn_units = (double)sum_ctx;
   return run_pass(c, a);
 }
 
@@ -588,6 +652,8 @@ int areal_sample_logprob(areal_ctx* c, int32_t n, const float* logits, const int
     d_pos = (const int32_t*)b.dev;
   }
   const float inv_t = 1.0f / temperature;
+  const bool sampled = c->prof_class == AREAL_K_SAMPLER && (c->prof_pass++ % c->prof_every) == 0;
+  ProfScope ps(c, AREAL_K_SAMPLER, -1, sampled, (double)n);
   HIP_TRY(c, launch_sampler(c->stream, n, c->cfg.vocab, logits, d_ids, d_pos, inv_t, top_p, seed, forced,
                             tokens_out, logp_behav, logp_full));
   return AREAL_OK;
@@ -690,6 +756,47 @@ int areal_adopt_seq(areal_ctx* c, int32_t id, int32_t len, int32_t fill_token) {
   s.versions.assign(len, -1);
   return AREAL_OK;
 }
+
+int areal_profile_begin(areal_ctx* c, int32_t klass, int32_t layer, int32_t every) {
+  if (!c) return AREAL_E_INVAL;
+  if (klass < 0 || klass >= AREAL_K_COUNT || layer < 0 || layer >= c->cfg.n_layers || every < 1)
+    return fail(c, AREAL_E_INVAL, "bad profile selection");
+  c->prof_class = klass;
+  c->prof_layer = layer;
+  c->prof_every = every;
+  c->prof_pass = 0;
+  c->prof_units = 0.0;
+  c->prof_used = 0;
+  return AREAL_OK;
+}
+
+int areal_profile_end(areal_ctx* c, int64_t* n_out, double* ms_out, double* units_out) {
+  if (!c) return AREAL_E_INVAL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  double ms = 0.0;
+  for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
+    float t = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&t, c->prof_events[i], c->prof_events[i + 1]));
+    ms += t;
+  }
+  if (n_out) *n_out = (int64_t)(c->prof_used / 2);
+  if (ms_out) *ms_out = ms;
+  if (units_out) *units_out = c->prof_units;
+  c->prof_class = -1;
+  c->prof_used = 0;
+  return AREAL_OK;
+}
+
+// ---- single-kernel entry points (include/areal_ops.h) -------------------------
+int areal_op_gemm(void* stream, const void* A, const void* W0, const void* W1, void* C, int32_t M,
+                  int32_t N, int32_t K, int32_t mode, int32_t cfg, int32_t splits) {
+  if (mode < 0 || mode > 2 || !A || !W0 || !C || (mode == 2 && !W1)) return AREAL_E_INVAL;
+  GemmW w{{(const bf16*)W0, mode == 2 ? (const bf16*)W1 : nullptr, nullptr}, {N, 0, 0}};
+  hipError_t e = launch_gemm_cfg((hipStream_t)stream, (const bf16*)A, w, C, M, N, K, N, (GemmMode)mode, cfg, splits);
+  if (e == hipErrorInvalidValue) return AREAL_E_INVAL;
+  return e == hipSuccess ? AREAL_OK : AREAL_E_HIP;
+}
+int areal_op_gemm_num_configs(void) { return gemm_num_configs(); }
 
 // ---- host-only test surface (include/areal_host.h) ---------------------------
 struct areal_kvalloc { KvAllocator a; };

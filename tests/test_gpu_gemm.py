@@ -1,0 +1,44 @@
+"""The projection GEMM kernel against a float64 product of the same bf16
+inputs, for every tile configuration, K split and output mode, on shapes that
+span several tiles with ragged edges in M, N and K."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def _ref(A, W):
+    return A.double().cpu().numpy() @ W.double().cpu().numpy().T
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (37, 344, 128), (200, 1000, 344), (256, 1536, 1536),
+                                   (300, 2048, 1000), (130, 520, 8960)])
+def test_gemm_all_configs(M, N, K):
+    import torch
+    from paper_2505_24298_amd import binding
+    L = binding.lib()
+    g = torch.Generator(device="cuda").manual_seed(M * 7 + N)
+    A = torch.randn((M, K), generator=g, device="cuda").to(torch.bfloat16)
+    W0 = (torch.randn((N, K), generator=g, device="cuda") * 0.05).to(torch.bfloat16)
+    W1 = (torch.randn((N, K), generator=g, device="cuda") * 0.05).to(torch.bfloat16)
+    ref0, ref1 = _ref(A, W0), _ref(A, W1)
+    scale = np.abs(ref0).max()
+    for cfg in list(range(L.areal_op_gemm_num_configs())) + [-1]:
+        if cfg >= 7 and K % 64:
+            # the direct-to-LDS configurations take whole 64-wide K slabs only
+            with pytest.raises(binding.ArealError):
+                binding.op_gemm(A, W0, None, torch.zeros((M, N), device="cuda"), 0, cfg, 1)
+            continue
+        for splits in (1, 3, -1):
+            C = torch.zeros((M, N), device="cuda")
+            binding.op_gemm(A, W0, None, C, 0, cfg, splits)
+            assert np.abs(C.cpu().numpy() - ref0).max() <= 2e-5 * scale * (K ** 0.5), (cfg, splits)
+            base = torch.randn((M, N), generator=g, device="cuda")
+            C = base.clone()
+            binding.op_gemm(A, W0, None, C, 1, cfg, splits)
+            assert np.abs(C.cpu().numpy() - (base.cpu().numpy() + ref0)).max() <= 2e-5 * scale * (K ** 0.5)
+        Cb = torch.zeros((M, N), device="cuda", dtype=torch.bfloat16)
+        binding.op_gemm(A, W0, W1, Cb, 2, cfg, 1)
+        want = ref0 / (1.0 + np.exp(-ref0)) * ref1
+        got = Cb.float().cpu().numpy()
+        assert np.abs(got - want).max() <= 2 ** -8 * np.abs(want).max() + 1e-6, cfg

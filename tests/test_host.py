@@ -20,7 +20,7 @@ def L():
 
 def _declared():
     names = set()
-    for h in ("areal.h", "areal_host.h"):
+    for h in ("areal.h", "areal_host.h", "areal_ops.h"):
         src = open(os.path.join(ROOT, "include", h)).read()
         src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
         names |= set(re.findall(r"\b(areal_[a-z0-9_]+)\s*\(", src))
