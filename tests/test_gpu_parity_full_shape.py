@@ -1,0 +1,79 @@
+"""Parity at the benchmark's real shape (Qwen2-1.5B dimensions, bf16 weights as
+bench.py generates them): 4 sequences, prompts of 64-128 tokens, 32 teacher-
+forced decode steps from a seeded token stream, one in-flight weight update.
+The oracle side is one dense float64 pass per weight version over the final
+token sequences (row t of that pass is the plain-definition logits for
+position t+1, as pinned on the small shape in test_oracle_decoder.py)."""
+import numpy as np
+import pytest
+
+from paper_2505_24298_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 2e-2
+LOGP_TOL = 1e-2
+
+
+def _to_oracle(w):
+    """torch bf16 device weights -> float64 numpy (exact)."""
+    cv = lambda t: t.float().cpu().numpy().astype(np.float64)
+    return dict(embed=cv(w["embed"]), lm_head=cv(w["lm_head"]), final_norm=cv(w["final_norm"]),
+                layers=[{k: cv(v) for k, v in lw.items()} for lw in w["layers"]])
+
+
+def test_qwen2_1p5b_shape_slice_with_interrupt():
+    import torch
+    from bench import device_weights
+    from oracle import decoder, sampler
+    from paper_2505_24298_amd import binding
+    cfg = synth.shape("qwen2-1.5b")
+    n_seq, n_new, t_int = 4, 32, 13
+    prompts = synth.make_prompts(cfg, n_seq, 1, 64, 128, seed=21)
+    rng = np.random.default_rng(22)
+    forced = rng.integers(0, cfg["vocab"], size=(n_seq, n_new)).astype(np.int32)
+    w0 = device_weights(torch, cfg, 0, "cuda:0")
+    w1 = device_weights(torch, cfg, 1001, "cuda:0", base=w0, scale=1e-3)
+    ids = list(range(n_seq))
+    plen = [len(p) for p in prompts]
+
+    # ---- GPU: prefill, forced decode, interrupt after t_int generated tokens ----
+    eng = binding.Areal(cfg, max_seqs=n_seq, max_seq_len=128 + n_new + 1, max_batch_tokens=256,
+                        kv_blocks=n_seq * 12)
+    eng.load_weights(w0, 0)
+    logits = eng.prefill(ids, prompts)
+    got_logits, got_lb, got_lf = [], [], []
+    for t in range(n_new):
+        if t == t_int:
+            live, logits, retok = eng.update_weights_interrupt(w1, 1)
+            assert live.tolist() == ids and retok == sum(plen) + n_seq * t_int
+            logits = logits.contiguous()
+        f = torch.from_numpy(forced[:, t].copy()).cuda()
+        toks, lb, lf = eng.sample_logprob(logits, ids, [plen[s] + t for s in ids], 1.0, 1.0, 0, forced_tokens=f)
+        got_logits.append(logits.cpu().numpy().copy())
+        got_lb.append(lb.cpu().numpy().copy())
+        got_lf.append(lf.cpu().numpy().copy())
+        logits = eng.decode_step(ids, toks)
+    for s in ids:
+        assert eng.get_tokens(s).tolist() == prompts[s].tolist() + forced[s].tolist()
+        assert eng.get_versions(s).tolist() == [-1] * plen[s] + [0] * t_int + [1] * (n_new - t_int)
+    eng.close()
+    got_logits = np.stack(got_logits)            # [n_new, n_seq, V]
+
+    # ---- oracle: dense pass per version over prompt + forced tokens ----
+    worst_logit = worst_lb = worst_lf = 0.0
+    for ver, (wd, steps) in enumerate([(w0, range(0, t_int)), (w1, range(t_int, n_new))]):
+        wo = _to_oracle(wd)
+        for s in ids:
+            seq = np.concatenate([prompts[s], forced[s, :-1]])
+            rows = [plen[s] - 1 + t for t in steps]
+            ref = decoder.forward(seq, wo, cfg, rows=rows)       # [len(steps), V]
+            for i, t in enumerate(steps):
+                worst_logit = max(worst_logit, float(np.abs(got_logits[t, s] - ref[i]).max()))
+                _, lb, lf = sampler.sample_row(ref[i].astype(np.float32), 1.0, 1.0, 0, s, plen[s] + t,
+                                               forced=int(forced[s, t]))
+                worst_lb = max(worst_lb, abs(float(got_lb[t][s]) - lb))
+                worst_lf = max(worst_lf, abs(float(got_lf[t][s]) - lf))
+        del wo
+    print(f"1.5B shape: logits {worst_logit:.2e}  logp_behav {worst_lb:.2e}  logp_full {worst_lf:.2e}")
+    assert worst_logit <= LOGIT_TOL and worst_lb <= LOGP_TOL and worst_lf <= LOGP_TOL
