@@ -49,6 +49,7 @@ extern "C" {
 
 #define AREAL_DTYPE_F32   0
 #define AREAL_DTYPE_BF16  1
+#define AREAL_DTYPE_F16   2
 
 #define AREAL_KV_BLOCK_TOKENS 16
 
@@ -61,9 +62,10 @@ typedef struct {
   int32_t max_seqs;            /* sequence ids are 0 .. max_seqs-1                        */
   int32_t max_seq_len;         /* prompt + generated tokens per sequence                  */
   int32_t max_batch_tokens;    /* rows of one forward pass; longer prefills are chunked   */
-  int32_t fp32_weights;        /* 1: areal_load_weights may be given float32 parameters,
-                                  which the library rounds to bf16 (nearest even) into
-                                  space reserved in the workspace                         */
+  int32_t convert_weights;     /* 1: parameter sets may be given as bf16 or float32; the
+                                  library converts them to half precision (nearest even)
+                                  into space reserved in the workspace.  0: only half-
+                                  precision sets, read in place                           */
   void*    kv_arena;           /* device; paged K/V pool, any size >= one block           */
   uint64_t kv_arena_bytes;
   void*    workspace;          /* device; >= areal_workspace_bytes(cfg), 256-B aligned    */
@@ -71,13 +73,18 @@ typedef struct {
   void*    hip_stream;         /* hipStream_t owned by the caller; NULL = default stream  */
 } areal_model_cfg;
 
-/* One parameter set.  All pointers are device pointers that stay valid and
- * unchanged until the next areal_load_weights / areal_update_weights_interrupt
- * has been called AND the stream has passed it (the library reads them in
- * place; with dtype F32 it reads them only during that call's conversion).
+/* One parameter set.  The matrix cores take half-precision (IEEE fp16)
+ * operands with float32 accumulation: the paper's precision (Table 3:
+ * parameters and KV cache fp16).  A set given as AREAL_DTYPE_F16 is read in
+ * place: its device pointers must stay valid and unchanged until the next
+ * areal_load_weights / areal_update_weights_interrupt has been called AND the
+ * stream has passed it.  A set given as bf16 or float32 is converted during the
+ * call that receives it (stream-ordered; bf16 values of magnitude >= 2^-14
+ * convert exactly, smaller ones round to the nearest half subnormal, larger
+ * than 65504 saturate) and is not read afterwards.
  * Per-layer arrays are host arrays of n_layers device pointers. */
 typedef struct {
-  int32_t dtype;                                    /* AREAL_DTYPE_BF16 or AREAL_DTYPE_F32   */
+  int32_t dtype;                                    /* AREAL_DTYPE_F16, _BF16 or _F32        */
   const void *embed;                                /* [vocab, hidden]                       */
   const void *lm_head;                              /* [vocab, hidden]; may equal embed      */
   const void *final_norm;                           /* [hidden]                              */

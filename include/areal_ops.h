@@ -17,8 +17,8 @@ extern "C" {
  * policy forward pass, Section 2 "LLM Training and Inference"):
  *   mode 0: C float32 [M,N]  = A W0^T
  *   mode 1: C float32 [M,N] += A W0^T
- *   mode 2: C bf16    [M,N]  = silu(A W0^T) * (A W1^T)      (W0 gate, W1 up)
- * A bf16 [M,K], W0/W1 bf16 [N,K], row-major, 16-byte aligned, K % 8 == 0.
+ *   mode 2: C half    [M,N]  = silu(A W0^T) * (A W1^T)      (W0 gate, W1 up)
+ * A half [M,K], W0/W1 half [N,K] (IEEE fp16), row-major, 16-byte aligned, K % 8 == 0.
  * cfg = tile configuration 0 .. areal_op_gemm_num_configs()-1, or -1 for the
  * library's own choice; splits = K split (>1 accumulates with float32 atomics:
  * in mode 0 C must be zero beforehand), or -1 for the library's choice.

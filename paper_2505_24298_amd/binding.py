@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libareal.so")
 
 OK, E_INVAL, E_NOMEM, E_STATE, E_HIP = 0, -1, -2, -3, -4
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 KV_BLOCK_TOKENS = 16
 (K_EMBED, K_RMSNORM, K_GEMM_QKV, K_ROPE_KVWRITE, K_ATTN_DECODE, K_ATTN_PREFILL, K_GEMM_O,
  K_GEMM_GATEUP, K_GEMM_DOWN, K_GEMM_LMHEAD, K_SAMPLER) = range(11)
@@ -32,7 +32,7 @@ class ModelCfg(C.Structure):
                 ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + [
         ("rope_theta", C.c_float), ("rms_eps", C.c_float),
         ("max_seqs", C.c_int32), ("max_seq_len", C.c_int32), ("max_batch_tokens", C.c_int32),
-        ("fp32_weights", C.c_int32),
+        ("convert_weights", C.c_int32),
         ("kv_arena", C.c_void_p), ("kv_arena_bytes", C.c_uint64),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64),
         ("hip_stream", C.c_void_p)]
@@ -112,14 +112,14 @@ def _i32(a):
     return a, a.ctypes.data_as(_I32P)
 
 
-def make_cfg(shape, max_seqs, max_seq_len, max_batch_tokens, fp32_weights=False):
+def make_cfg(shape, max_seqs, max_seq_len, max_batch_tokens, convert_weights=True):
     cfg = ModelCfg()
     for k in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab"):
         setattr(cfg, k, int(shape[k]))
     cfg.rope_theta = float(shape["rope_theta"])
     cfg.rms_eps = float(shape["rms_eps"])
     cfg.max_seqs, cfg.max_seq_len, cfg.max_batch_tokens = int(max_seqs), int(max_seq_len), int(max_batch_tokens)
-    cfg.fp32_weights = int(bool(fp32_weights))
+    cfg.convert_weights = int(bool(convert_weights))
     return cfg
 
 
@@ -128,7 +128,7 @@ class Areal:
     the C entry points without the prefix."""
 
     def __init__(self, shape, max_seqs, max_seq_len, max_batch_tokens, kv_blocks,
-                 fp32_weights=False, device="cuda:0"):
+                 convert_weights=True, device="cuda:0"):
         import torch
         self.torch = torch
         self.device = torch.device(device)
@@ -136,7 +136,7 @@ class Areal:
         self.vocab = int(shape["vocab"])
         self.max_seqs = int(max_seqs)
         self.L = lib()
-        cfg = make_cfg(shape, max_seqs, max_seq_len, max_batch_tokens, fp32_weights)
+        cfg = make_cfg(shape, max_seqs, max_seq_len, max_batch_tokens, convert_weights)
         ws_bytes = self.L.areal_workspace_bytes(C.byref(cfg))
         blk_bytes = self.L.areal_kv_block_bytes(C.byref(cfg))
         if ws_bytes == 0 or blk_bytes == 0:
@@ -173,11 +173,12 @@ class Areal:
     # -- weights -----------------------------------------------------------
     def _weights_struct(self, w):
         """w: dict like synth.make_weights but of torch device tensors (all
-        float32 or all bfloat16)."""
+        of one dtype: float32, bfloat16 or float16)."""
         torch = self.torch
         dt = w["embed"].dtype
-        if dt not in (torch.float32, torch.bfloat16):
-            raise ArealError(E_INVAL, "weights must be float32 or bfloat16 tensors")
+        codes = {torch.float32: DTYPE_F32, torch.bfloat16: DTYPE_BF16, torch.float16: DTYPE_F16}
+        if dt not in codes:
+            raise ArealError(E_INVAL, "weights must be float32, bfloat16 or float16 tensors")
         keep = []
 
         def ptr(t):
@@ -186,7 +187,7 @@ class Areal:
             return t.data_ptr()
 
         s = Weights()
-        s.dtype = DTYPE_F32 if dt == torch.float32 else DTYPE_BF16
+        s.dtype = codes[dt]
         s.embed, s.lm_head, s.final_norm = ptr(w["embed"]), ptr(w["lm_head"]), ptr(w["final_norm"])
         nl = len(w["layers"])
         names = ["wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "norm_attn", "norm_ffn"]

@@ -3,10 +3,10 @@
 // One wavefront owns 16 "rows" (decode: the <=16 query heads that share one
 // KV head, for one sequence; prefill: 16 consecutive query positions of one
 // head) and walks KV blocks of 16 tokens with an online softmax:
-//   S^T[token, row] = K_tile . Q^T      v_mfma_f32_16x16x32_bf16, K straight
+//   S^T[token, row] = K_tile . Q^T      v_mfma_f32_16x16x32_f16, K straight
 //                                       from HBM in its row-major tile layout
 //   P = exp2(S^T - m)                   float32, per-row running max / sum
-//   O[row, :] += P . V_tile             v_mfma_f32_16x16x16_bf16; the
+//   O[row, :] += P . V_tile             v_mfma_f32_16x16x16_f16; the 
 //                                       accumulator layout of S^T is already
 //                                       the A-operand layout of this product,
 //                                       and the V tile is stored in its
@@ -21,32 +21,31 @@ constexpr int NB = 2;   // KV blocks per softmax update (32 tokens)
 
 template <int D>
 struct KvFrag {
-  bf16x8 k[NB][D / 32];
-  bf16x8 v[NB][D / 32];
+  f16x8 k[NB][D / 32];
+  f16x8 v[NB][D / 32];
 };
 
-__device__ __forceinline__ f32x4 mfma_qk(bf16x8 a, bf16x8 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+__device__ __forceinline__ f32x4 mfma_qk(f16x8 a, f16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
-__device__ __forceinline__ f32x4 mfma_pv(bf16x4 p, bf16x4 v, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, p),
-                                                    __builtin_bit_cast(s16x4, v), c, 0, 0, 0);
+__device__ __forceinline__ f32x4 mfma_pv(f16x4 p, f16x4 v, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16f16(p, v, c, 0, 0, 0);
 }
 
 // Issue the loads of NB blocks starting at logical block `b` (blocks >= b_end
 // are skipped and read as zero).
 template <int D>
-__device__ __forceinline__ void load_group(KvFrag<D>& f, const bf16* __restrict__ arena,
+__device__ __forceinline__ void load_group(KvFrag<D>& f, const f16* __restrict__ arena,
                                            const KvGeom& geom, const int32_t* __restrict__ table,
                                            int b, int b_end, int kvh, int lane) {
   const int g = lane >> 4, j = lane & 15;
-  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
   for (int u = 0; u < NB; ++u) {
     if (b + u < b_end) {
       const int blk = table[b + u];
-      const bf16* kt = arena + kv_tile_off(geom, blk, kvh, 0) + j * D + g * (D / 4);
-      const bf16* vt = arena + kv_tile_off(geom, blk, kvh, 1) + lane * (D / 4);
+      const f16* kt = arena + kv_tile_off(geom, blk, kvh, 0) + j * D + g * (D / 4);
+      const f16* vt = arena + kv_tile_off(geom, blk, kvh, 1) + lane * (D / 4);
 #pragma unroll
       for (int c = 0; c < D / 32; ++c) {
         f.k[u][c] = ld8(kt + c * 8);
@@ -68,7 +67,7 @@ __device__ __forceinline__ void load_group(KvFrag<D>& f, const bf16* __restrict_
 //   m, l   : running max (log2 domain) and this lane's share of the running sum
 //   o      : accumulator, lane (g, jj) holds rows 4g+v, dims 16n+jj
 template <int D>
-__device__ __forceinline__ void attend_group(const KvFrag<D>& f, const bf16x8 (&qf)[D / 32], int b,
+__device__ __forceinline__ void attend_group(const KvFrag<D>& f, const f16x8 (&qf)[D / 32], int b,
                                              int row_pos, float scale_log2, float& m, float& l,
                                              f32x4 (&o)[D / 16], int lane) {
   const int g = lane >> 4;
@@ -93,14 +92,14 @@ __device__ __forceinline__ void attend_group(const KvFrag<D>& f, const bf16x8 (&
   const float alpha = __builtin_amdgcn_exp2f(m - m_use);   // m = -inf -> 0
   m = m_new;
   float psum = 0.f;
-  bf16x4 p[NB];
+  f16x4 p[NB];
 #pragma unroll
   for (int u = 0; u < NB; ++u)
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const float e = __builtin_amdgcn_exp2f(s[u][v] - m_use);
       psum += e;
-      p[u][v] = f2bf(e);
+      p[u][v] = f2h(e);
     }
   l = l * alpha + psum;
   // rescale the accumulator rows: row 4g+v needs the alpha held by lanes with (lane&15)==4g+v
@@ -115,9 +114,9 @@ __device__ __forceinline__ void attend_group(const KvFrag<D>& f, const bf16x8 (&
   for (int u = 0; u < NB; ++u)
 #pragma unroll
     for (int n = 0; n < D / 16; ++n) {
-      const bf16x8 vv = f.v[u][n >> 1];
-      bf16x4 vh;
-      if (n & 1) vh = bf16x4{vv[4], vv[5], vv[6], vv[7]}; else vh = bf16x4{vv[0], vv[1], vv[2], vv[3]};
+      const f16x8 vv = f.v[u][n >> 1];
+      f16x4 vh;
+      if (n & 1) vh = f16x4{vv[4], vv[5], vv[6], vv[7]}; else vh = f16x4{vv[0], vv[1], vv[2], vv[3]};
       o[n] = mfma_pv(p[u], vh, o[n]);
     }
 }
@@ -125,9 +124,9 @@ __device__ __forceinline__ void attend_group(const KvFrag<D>& f, const bf16x8 (&
 // ------------------------------------------------------------------ decode
 template <int D>
 __global__ __launch_bounds__(256) void attn_decode_kernel(
-    const bf16* __restrict__ q, RowMeta rm, SeqState st, const bf16* __restrict__ arena, KvGeom geom,
+    const f16* __restrict__ q, RowMeta rm, SeqState st, const f16* __restrict__ arena, KvGeom geom,
     int nq, int chunk, int n_splits, float scale_log2, float* __restrict__ part_o,
-    float* __restrict__ part_ml, bf16* __restrict__ out) {
+    float* __restrict__ part_ml, f16* __restrict__ out) {
   __shared__ float sm[4][16], sl[4][16];
   __shared__ float so[4][16][D];
   const int i = blockIdx.z, kvh = blockIdx.y, split = blockIdx.x;
@@ -141,10 +140,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   const int G = nq / geom.n_kv_heads;
   const int32_t* table = st.table + (int64_t)rm.slot[i] * st.max_blocks;
 
-  bf16x8 qf[D / 32];
+  f16x8 qf[D / 32];
   {
-    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const bf16* qp = q + ((int64_t)i * nq + kvh * G + j) * D + g * (D / 4);
+    const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    const f16* qp = q + ((int64_t)i * nq + kvh * G + j) * D + g * (D / 4);
 #pragma unroll
     for (int c = 0; c < D / 32; ++c) qf[c] = j < G ? ld8(qp + c * 8) : zero8;
   }
@@ -185,7 +184,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     }
     const int head = kvh * G + h;
     if (n_splits == 1) {
-      out[((int64_t)i * nq + head) * D + dd] = f2bf(O / L);
+      out[((int64_t)i * nq + head) * D + dd] = f2h(O / L);
     } else {
       const int64_t pi = ((int64_t)i * nq + head) * n_splits + split;
       part_o[pi * D + dd] = O;
@@ -199,7 +198,7 @@ template <int D>
 __global__ __launch_bounds__(D) void attn_merge_kernel(const float* __restrict__ part_o,
                                                        const float* __restrict__ part_ml, RowMeta rm,
                                                        int nq, int chunk, int n_splits,
-                                                       bf16* __restrict__ out) {
+                                                       f16* __restrict__ out) {
   const int i = blockIdx.x / nq;
   const int ctx = rm.pos[i] + 1;
   const int ns = min(n_splits, (ctx + chunk - 1) / chunk);
@@ -212,14 +211,14 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(const float* __restrict__
     L += part_ml[(base + s) * 2 + 1] * sc;
     O += part_o[(base + s) * D + threadIdx.x] * sc;
   }
-  out[(int64_t)blockIdx.x * D + threadIdx.x] = f2bf(O / L);
+  out[(int64_t)blockIdx.x * D + threadIdx.x] = f2h(O / L);
 }
 
 // ----------------------------------------------------------------- prefill
 template <int D>
 __global__ __launch_bounds__(256) void attn_prefill_kernel(
-    const bf16* __restrict__ q, const AttnWork* __restrict__ work, SeqState st,
-    const bf16* __restrict__ arena, KvGeom geom, int nq, float scale_log2, bf16* __restrict__ out) {
+    const f16* __restrict__ q, const AttnWork* __restrict__ work, SeqState st,
+    const f16* __restrict__ arena, KvGeom geom, int nq, float scale_log2, f16* __restrict__ out) {
   const AttnWork wk = work[blockIdx.x];
   const int head = blockIdx.y, kvh = head / (nq / geom.n_kv_heads);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -233,10 +232,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
   const int b1 = last_pos / kBlockTokens + 1;
   const int32_t* table = st.table + (int64_t)wk.slot * st.max_blocks;
 
-  bf16x8 qf[D / 32];
+  f16x8 qf[D / 32];
   {
-    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const bf16* qp = q + ((int64_t)(wk.row0 + my_r) * nq + head) * D + g * (D / 4);
+    const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    const f16* qp = q + ((int64_t)(wk.row0 + my_r) * nq + head) * D + g * (D / 4);
 #pragma unroll
     for (int c = 0; c < D / 32; ++c) qf[c] = row_ok ? ld8(qp + c * 8) : zero8;
   }
@@ -264,10 +263,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
   for (int v = 0; v < 4; ++v) {
     const int r = r_first + 4 * g + v;
     if (r < wk.n_rows) {
-      bf16* op = out + ((int64_t)(wk.row0 + r) * nq + head) * D;
+      f16* op = out + ((int64_t)(wk.row0 + r) * nq + head) * D;
       const float inv = 1.0f / lo[v];
 #pragma unroll
-      for (int n = 0; n < D / 16; ++n) op[16 * n + j] = f2bf(o[n][v] * inv);
+      for (int n = 0; n < D / 16; ++n) op[16 * n + j] = f2h(o[n][v] * inv);
     }
   }
 }
@@ -281,9 +280,9 @@ static bool geom_ok(const KvGeom& g, int nq) {
   return true;
 }
 
-hipError_t launch_attn_decode(hipStream_t s, const bf16* q, int M, RowMeta rm, SeqState st,
-                              const bf16* arena_layer, KvGeom geom, int n_q_heads, int chunk,
-                              int n_splits, float* part_o, float* part_ml, bf16* out) {
+hipError_t launch_attn_decode(hipStream_t s, const f16* q, int M, RowMeta rm, SeqState st,
+                              const f16* arena_layer, KvGeom geom, int n_q_heads, int chunk,
+                              int n_splits, float* part_o, float* part_ml, f16* out) {
   if (M <= 0 || !geom_ok(geom, n_q_heads) || chunk <= 0 || chunk % (4 * NB * kBlockTokens) ||
       n_splits <= 0 || (n_splits > 1 && (!part_o || !part_ml)))
     return hipErrorInvalidValue;
@@ -304,9 +303,9 @@ hipError_t launch_attn_decode(hipStream_t s, const bf16* q, int M, RowMeta rm, S
   return hipGetLastError();
 }
 
-hipError_t launch_attn_prefill(hipStream_t s, const bf16* q, const AttnWork* work, int n_work,
-                               SeqState st, const bf16* arena_layer, KvGeom geom, int n_q_heads,
-                               bf16* out) {
+hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work, int n_work,
+                               SeqState st, const f16* arena_layer, KvGeom geom, int n_q_heads,
+                               f16* out) {
   if (n_work <= 0 || !geom_ok(geom, n_q_heads)) return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)geom.head_dim);
   dim3 grid(n_work, n_q_heads);

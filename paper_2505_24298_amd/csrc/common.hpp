@@ -5,11 +5,13 @@
 
 namespace areal {
 
-typedef __bf16 bf16;
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short  s16x4 __attribute__((ext_vector_type(4)));
+// Matrix-core operands (weights, activations, K/V) are IEEE half precision; all
+// accumulation, the residual stream, softmax statistics and logits are float32.
+typedef _Float16 f16;
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16_in;   // only as an input format of parameter sets
 typedef float  f32x4 __attribute__((ext_vector_type(4)));
 typedef float  f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -18,11 +20,11 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kWave = 64;
 constexpr int kBlockTokens = 16;   // tokens per KV block
 
-__device__ __forceinline__ float bf2f(bf16 x) { return (float)x; }
-__device__ __forceinline__ bf16 f2bf(float x) { return (bf16)x; }   // round to nearest even
+__device__ __forceinline__ float h2f(f16 x) { return (float)x; }
+__device__ __forceinline__ f16 f2h(float x) { return (f16)x; }   // round to nearest even
 
-// 16-byte global load of 8 bf16
-__device__ __forceinline__ bf16x8 ld8(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+// 16-byte global load of 8 halves
+__device__ __forceinline__ f16x8 ld8(const f16* p) { return *reinterpret_cast<const f16x8*>(p); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -36,7 +38,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- paged KV arena addressing --------------------------------------------
-// arena = [layer][block][kv_head][K tile | V tile], tiles of 16*d bf16.
+// arena = [layer][block][kv_head][K tile | V tile], tiles of 16*d halves.
 //   K tile: [token 0..15][d]                       (row-major)
 //   V tile: [lane 0..63][n 0..d/16-1][t 0..3] with lane = g*16 + j holding
 //           V[token 4g+t][dim 16n+j]: exactly the B operand of the 16x16x16

@@ -1,5 +1,5 @@
 // Small HBM-bound kernels of the decoder block: token embedding, RMSNorm,
-// rotary embedding + paged K/V store, float32 -> bf16 conversion.
+// rotary embedding + paged K/V store, parameter conversion to half precision.
 #include "kernels.hpp"
 
 namespace areal {
@@ -7,7 +7,7 @@ namespace areal {
 // h[r,:] = E[token(r),:] as float32.  In a decode step (tokens_in != null) the
 // kernel also records the appended token in the history and installs the KV
 // block the host reserved for a sequence that crossed a block boundary.
-__global__ __launch_bounds__(256) void embed_kernel(const bf16* __restrict__ E, int H, int V,
+__global__ __launch_bounds__(256) void embed_kernel(const f16* __restrict__ E, int H, int V,
                                                     RowMeta rm, const int32_t* __restrict__ tokens_in,
                                                     const int32_t* __restrict__ new_block, SeqState st,
                                                     float* __restrict__ h) {
@@ -26,29 +26,29 @@ __global__ __launch_bounds__(256) void embed_kernel(const bf16* __restrict__ E, 
     int nb = new_block[r];
     if (nb >= 0) st.table[(int64_t)slot * st.max_blocks + pos / kBlockTokens] = nb;
   }
-  const bf16* src = E + (int64_t)tok * H;
+  const f16* src = E + (int64_t)tok * H;
   float* dst = h + (int64_t)r * H;
   for (int c = threadIdx.x * 8; c < H; c += 256 * 8) {
-    bf16x8 v = ld8(src + c);
-    f32x4 a = {bf2f(v[0]), bf2f(v[1]), bf2f(v[2]), bf2f(v[3])};
-    f32x4 b = {bf2f(v[4]), bf2f(v[5]), bf2f(v[6]), bf2f(v[7])};
+    f16x8 v = ld8(src + c);
+    f32x4 a = {h2f(v[0]), h2f(v[1]), h2f(v[2]), h2f(v[3])};
+    f32x4 b = {h2f(v[4]), h2f(v[5]), h2f(v[6]), h2f(v[7])};
     *reinterpret_cast<f32x4*>(dst + c) = a;
     *reinterpret_cast<f32x4*>(dst + c + 4) = b;
   }
 }
 
-hipError_t launch_embed(hipStream_t s, const bf16* embed, int hidden, int vocab, int M, RowMeta rm,
+hipError_t launch_embed(hipStream_t s, const f16* embed, int hidden, int vocab, int M, RowMeta rm,
                         const int32_t* tokens_in, const int32_t* new_block, SeqState st, float* h) {
   if (M <= 0 || hidden % 8 || vocab <= 0) return hipErrorInvalidValue;
   embed_kernel<<<M, 256, 0, s>>>(embed, hidden, vocab, rm, tokens_in, new_block, st, h);
   return hipGetLastError();
 }
 
-// y = x / sqrt(mean(x^2) + eps) * gain, one wavefront per row, bf16 out.
+// y = x / sqrt(mean(x^2) + eps) * gain, one wavefront per row, f16 out.
 // src_rows (optional) gathers: output row r is computed from input row src_rows[r].
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x,
-                                                      const bf16* __restrict__ gain,
-                                                      bf16* __restrict__ y, int M, int H, float eps,
+                                                      const f16* __restrict__ gain,
+                                                      f16* __restrict__ y, int M, int H, float eps,
                                                       const int32_t* __restrict__ src_rows,
                                                       float* __restrict__ zero_out, int zero_cols) {
   const int lane = threadIdx.x & 63;
@@ -63,14 +63,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   }
   ss = wave_sum(ss);
   const float r = 1.0f / sqrtf(ss / (float)H + eps);
-  bf16* yp = y + (int64_t)row * H;
+  f16* yp = y + (int64_t)row * H;
   for (int c = lane * 4; c < H; c += 256) {
     f32x4 v = *reinterpret_cast<const f32x4*>(xp + c);
-    bf16x4 g = *reinterpret_cast<const bf16x4*>(gain + c);
-    bf16x4 o;
+    f16x4 g = *reinterpret_cast<const f16x4*>(gain + c);
+    f16x4 o;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = f2bf(v[i] * r * bf2f(g[i]));
-    *reinterpret_cast<bf16x4*>(yp + c) = o;
+    for (int i = 0; i < 4; ++i) o[i] = f2h(v[i] * r * h2f(g[i]));
+    *reinterpret_cast<f16x4*>(yp + c) = o;
   }
   if (zero_out) {
     float* zp = zero_out + (int64_t)row * zero_cols;
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   }
 }
 
-hipError_t launch_rmsnorm(hipStream_t s, const float* x, const bf16* gain, bf16* y, int M, int hidden,
+hipError_t launch_rmsnorm(hipStream_t s, const float* x, const f16* gain, f16* y, int M, int hidden,
                           float eps, const int32_t* src_rows, float* zero_out, int zero_cols) {
   if (M <= 0 || hidden % 4 || (zero_out && zero_cols % 4)) return hipErrorInvalidValue;
   rmsnorm_kernel<<<(M + 3) / 4, 256, 0, s>>>(x, gain, y, M, hidden, eps, src_rows, zero_out, zero_cols);
@@ -88,11 +88,11 @@ hipError_t launch_rmsnorm(hipStream_t s, const float* x, const bf16* gain, bf16*
 
 // Adds the optional QKV bias, rotates q and k heads (rotate-half pairing: dims
 // j and j + d/2 turn by pos * theta^(-2j/d), angles from a host-built table),
-// writes q as bf16 [M, nq, d] and stores k, v into the sequence's KV block.
+// writes q as f16 [M, nq, d] and stores k, v into the sequence's KV block.
 __global__ __launch_bounds__(256) void rope_kvwrite_kernel(
-    const float* __restrict__ qkv, RowMeta rm, SeqState st, const bf16* __restrict__ bq,
-    const bf16* __restrict__ bk, const bf16* __restrict__ bv, const float* __restrict__ cos_tab,
-    const float* __restrict__ sin_tab, bf16* __restrict__ q_out, bf16* __restrict__ arena_layer,
+    const float* __restrict__ qkv, RowMeta rm, SeqState st, const f16* __restrict__ bq,
+    const f16* __restrict__ bk, const f16* __restrict__ bv, const float* __restrict__ cos_tab,
+    const float* __restrict__ sin_tab, f16* __restrict__ q_out, f16* __restrict__ arena_layer,
     KvGeom geom, int nq) {
   const int r = blockIdx.x;
   const int d = geom.head_dim, half = d >> 1, nkv = geom.n_kv_heads;
@@ -108,35 +108,35 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(
     const int head = idx / half, j = idx - head * half;
     float x1 = row[head * d + j], x2 = row[head * d + j + half];
     if (bq) {
-      const bf16* b = head < nq ? bq + head * d : bk + (head - nq) * d;
-      x1 += bf2f(b[j]);
-      x2 += bf2f(b[j + half]);
+      const f16* b = head < nq ? bq + head * d : bk + (head - nq) * d;
+      x1 += h2f(b[j]);
+      x2 += h2f(b[j + half]);
     }
     const float c = ct[j], sv = sn[j];
     const float y1 = x1 * c - x2 * sv, y2 = x2 * c + x1 * sv;
     if (head < nq) {
-      bf16* qo = q_out + ((int64_t)r * nq + head) * d;
-      qo[j] = f2bf(y1);
-      qo[j + half] = f2bf(y2);
+      f16* qo = q_out + ((int64_t)r * nq + head) * d;
+      qo[j] = f2h(y1);
+      qo[j + half] = f2h(y2);
     } else {
-      bf16* kt = arena_layer + kv_tile_off(geom, blk, head - nq, 0) + tin * d;
-      kt[j] = f2bf(y1);
-      kt[j + half] = f2bf(y2);
+      f16* kt = arena_layer + kv_tile_off(geom, blk, head - nq, 0) + tin * d;
+      kt[j] = f2h(y1);
+      kt[j + half] = f2h(y2);
     }
   }
   const float* vrow = row + (nq + nkv) * d;
   for (int idx = threadIdx.x; idx < nkv * d; idx += 256) {
     const int kvh = idx / d, dim = idx - kvh * d;
     float v = vrow[idx];
-    if (bv) v += bf2f(bv[idx]);
-    bf16* vt = arena_layer + kv_tile_off(geom, blk, kvh, 1);
-    vt[v_tile_index(d, tin, dim)] = f2bf(v);
+    if (bv) v += h2f(bv[idx]);
+    f16* vt = arena_layer + kv_tile_off(geom, blk, kvh, 1);
+    vt[v_tile_index(d, tin, dim)] = f2h(v);
   }
 }
 
 hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
-                               const bf16* bq, const bf16* bk, const bf16* bv, const float* cos_tab,
-                               const float* sin_tab, bf16* q_out, bf16* arena_layer, KvGeom geom,
+                               const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
+                               const float* sin_tab, f16* q_out, f16* arena_layer, KvGeom geom,
                                int n_q_heads) {
   if (M <= 0 || geom.head_dim % 16 || (bq && (!bk || !bv))) return hipErrorInvalidValue;
   rope_kvwrite_kernel<<<M, 256, 0, s>>>(qkv, rm, st, bq, bk, bv, cos_tab, sin_tab, q_out, arena_layer,
@@ -144,18 +144,29 @@ hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta r
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ src,
-                                                          bf16* __restrict__ dst, int64_t n) {
+// Parameter sets arrive as float32 or bf16 and are held as halves for the
+// matrix cores (round to nearest even; bf16 values with |w| >= 2^-14 convert
+// exactly).  Magnitudes beyond the half range saturate to +-65504.
+template <typename SRC>
+__global__ __launch_bounds__(256) void to_f16_kernel(const SRC* __restrict__ src, f16* __restrict__ dst,
+                                                     int64_t n) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * 256;
-  for (; i < n; i += stride) dst[i] = f2bf(src[i]);
+  for (; i < n; i += stride) {
+    float v = (float)src[i];
+    v = fminf(fmaxf(v, -65504.0f), 65504.0f);
+    dst[i] = f2h(v);
+  }
 }
 
-hipError_t launch_f32_to_bf16(hipStream_t s, const float* src, bf16* dst, int64_t n) {
-  if (n <= 0) return hipErrorInvalidValue;
+hipError_t launch_to_f16(hipStream_t s, const void* src, int src_is_bf16, f16* dst, int64_t n) {
+  if (n <= 0 || !src || !dst) return hipErrorInvalidValue;
   int64_t blocks = (n + 255) / 256;
-  if (blocks > 4096) blocks = 4096;
-  f32_to_bf16_kernel<<<(int)blocks, 256, 0, s>>>(src, dst, n);
+  if (blocks > 8192) blocks = 8192;
+  if (src_is_bf16)
+    to_f16_kernel<bf16_in><<<(int)blocks, 256, 0, s>>>(reinterpret_cast<const bf16_in*>(src), dst, n);
+  else
+    to_f16_kernel<float><<<(int)blocks, 256, 0, s>>>(reinterpret_cast<const float*>(src), dst, n);
   return hipGetLastError();
 }
 

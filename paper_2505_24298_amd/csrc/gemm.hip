@@ -1,8 +1,8 @@
-// bf16 x bf16 -> float32 GEMM on the gfx950 matrix cores.
+// f16 x f16 -> float32 GEMM on the gfx950 matrix cores.
 //   C[M,N] (+)= A[M,K] * W[N,K]^T      (both operands K-contiguous)
 // Work-group tile BM x BN x 64 staged through LDS with register prefetch of
 // the next K-slab; WM x WN wavefronts, each computing (BM/WM) x (BN/WN) with
-// v_mfma_f32_32x32x16_bf16.  The K range can be split over work-groups
+// v_mfma_f32_32x32x16_f16.  The K range can be split over work-groups
 // (float32 atomic accumulation into C) so that skinny decode-shape products
 // still fill 256 compute units; the block id -> tile map keeps the row tiles
 // that share a weight panel on one XCD (one L2).
@@ -20,7 +20,7 @@ constexpr int LDS_K = BK + 8;   // row stride in elements (144 B): conflict-free
 // Row `b` of the W tile -> pointer to that row of the (segmented) weight, or
 // null when it lies outside the matrix.
 template <int BN, int MODE>
-__device__ __forceinline__ const bf16* w_row_ptr(const GemmW& W, int tile_n, int b, int N, int K) {
+__device__ __forceinline__ const f16* w_row_ptr(const GemmW& W, int tile_n, int b, int N, int K) {
   if (MODE == GEMM_SWIGLU_BF16) {
     // every 64 tile rows = 32 gate rows then 32 up rows of the same 32 features
     const int grp = b >> 6, within = b & 63;
@@ -39,7 +39,7 @@ __device__ __forceinline__ const bf16* w_row_ptr(const GemmW& W, int tile_n, int
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
 template <int BM, int BN, int WM, int WN, int MODE, bool RAGGED_K>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const bf16* __restrict__ A, GemmW W,
+__global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const f16* __restrict__ A, GemmW W,
                                                             void* __restrict__ Cv, int M, int N, int K,
                                                             int ldc, int m_tiles, int n_tiles,
                                                             int slabs_per_split, int atomic) {
@@ -48,8 +48,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const bf16* __restri
   constexpr int ACH = BM * 8 / NT, BCH = BN * 8 / NT;   // 16-B chunks per thread per slab
   static_assert(TM >= 1 && TN >= 1 && ACH >= 1 && BCH >= 1, "tile too small for the wave grid");
   static_assert(MODE != GEMM_SWIGLU_BF16 || (TN % 2 == 0), "SwiGLU needs gate+up in one wave tile");
-  __shared__ __attribute__((aligned(16))) bf16 sA[2][BM * LDS_K];
-  __shared__ __attribute__((aligned(16))) bf16 sB[2][BN * LDS_K];
+  __shared__ __attribute__((aligned(16))) f16 sA[2][BM * LDS_K];
+  __shared__ __attribute__((aligned(16))) f16 sB[2][BN * LDS_K];
 
   // block id -> (row tile, column tile, K split): ids that differ by a multiple
   // of 8 sit on the same XCD; the row tiles of one weight panel are adjacent there.
@@ -69,8 +69,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const bf16* __restri
 
   // Rows outside the matrix are clamped to a valid row: they only feed
   // accumulator rows / columns that are never stored.
-  const bf16* pa[ACH];
-  const bf16* pb[BCH];
+  const f16* pa[ACH];
+  const f16* pb[BCH];
 #pragma unroll
   for (int i = 0; i < ACH; ++i) {
     const int m = min(m0 + r0 + RSTEP * i, M - 1);
@@ -78,23 +78,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const bf16* __restri
   }
 #pragma unroll
   for (int i = 0; i < BCH; ++i) {
-    const bf16* p = w_row_ptr<BN, MODE>(W, tile_n, r0 + RSTEP * i, N, K);
+    const f16* p = w_row_ptr<BN, MODE>(W, tile_n, r0 + RSTEP * i, N, K);
     if (!p) p = w_row_ptr<BN, MODE>(W, 0, 0, N, K);
     pb[i] = p + kc * 8;
   }
 
-  struct Slab { bf16x8 a[ACH], b[BCH]; };
+  struct Slab { f16x8 a[ACH], b[BCH]; };
   // RAGGED_K (K % 64 != 0; K % 8 == 0 always): a 16-byte chunk is all inside or
   // all outside the row; outside chunks are fetched from the row start and zeroed.
   auto load_slab = [&](Slab& r, int k0) {
     if (RAGGED_K) {
-      const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+      const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
       const bool kin = k0 + kc * 8 < K;
       const int ko = kin ? k0 : -kc * 8;
 #pragma unroll
-      for (int i = 0; i < BCH; ++i) { const bf16x8 v = ld8(pb[i] + ko); r.b[i] = kin ? v : zero8; }
+      for (int i = 0; i < BCH; ++i) { const f16x8 v = ld8(pb[i] + ko); r.b[i] = kin ? v : zero8; }
 #pragma unroll
-      for (int i = 0; i < ACH; ++i) { const bf16x8 v = ld8(pa[i] + ko); r.a[i] = kin ? v : zero8; }
+      for (int i = 0; i < ACH; ++i) { const f16x8 v = ld8(pa[i] + ko); r.a[i] = kin ? v : zero8; }
     } else {
 #pragma unroll
       for (int i = 0; i < BCH; ++i) r.b[i] = ld8(pb[i] + k0);
@@ -105,10 +105,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const bf16* __restri
   auto store_slab = [&](const Slab& r, int buf) {
 #pragma unroll
     for (int i = 0; i < ACH; ++i)
-      *reinterpret_cast<bf16x8*>(&sA[buf][(r0 + RSTEP * i) * LDS_K + kc * 8]) = r.a[i];
+      *reinterpret_cast<f16x8*>(&sA[buf][(r0 + RSTEP * i) * LDS_K + kc * 8]) = r.a[i];
 #pragma unroll
     for (int i = 0; i < BCH; ++i)
-      *reinterpret_cast<bf16x8*>(&sB[buf][(r0 + RSTEP * i) * LDS_K + kc * 8]) = r.b[i];
+      *reinterpret_cast<f16x8*>(&sB[buf][(r0 + RSTEP * i) * LDS_K + kc * 8]) = r.b[i];
   };
 
   f32x16 acc[TM][TN];
@@ -123,20 +123,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const bf16* __restri
   auto compute = [&](int buf) {
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[TM], fb[TN];
+      f16x8 fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8*>(
+        fa[i] = *reinterpret_cast<const f16x8*>(
             &sA[buf][(wm * (BM / WM) + i * 32 + fr) * LDS_K + kk * 16 + fh * 8]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        fb[j] = *reinterpret_cast<const bf16x8*>(
+        fb[j] = *reinterpret_cast<const f16x8*>(
             &sB[buf][(wn * (BN / WN) + j * 32 + fr) * LDS_K + kk * 16 + fh * 8]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
   };
 
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const bf16* __restri
 
   // D layout of the 32x32 tile: lane (fh, fr) holds column fr, rows 8*(v/4) + 4*fh + v%4.
   if (MODE == GEMM_SWIGLU_BF16) {
-    bf16* C = reinterpret_cast<bf16*>(Cv);
+    f16* C = reinterpret_cast<f16*>(Cv);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const bf16* __restri
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
           if (m < M && f < N)
-            C[(int64_t)m * ldc + f] = f2bf(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
+            C[(int64_t)m * ldc + f] = f2h(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
         }
       }
   } else {
@@ -239,7 +239,7 @@ __device__ __forceinline__ void wait_vmcnt(int n) {
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES, int MODE>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const bf16* __restrict__ A, GemmW W,
+__global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __restrict__ A, GemmW W,
                                                                 void* __restrict__ Cv, int M, int N,
                                                                 int K, int ldc, int m_tiles,
                                                                 int n_tiles, int slabs_per_split,
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const bf16* __re
   const int m0 = tile_m * BM;
 
   // this wave's share of the row groups: GA/NW groups of A, then GB/NW of B
-  const bf16* src[LPS];
+  const f16* src[LPS];
   int dst_off[LPS];
   {
     const int rin = lane >> 3;                          // row inside the group
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const bf16* __re
         src[i] = A + (int64_t)m * K + chunk * 8;
         dst_off[i] = gi * GROUP_BYTES;
       } else {
-        const bf16* p = w_row_ptr<BN, MODE>(W, tile_n, row, N, K);
+        const f16* p = w_row_ptr<BN, MODE>(W, tile_n, row, N, K);
         if (!p) p = w_row_ptr<BN, MODE>(W, 0, 0, N, K);
         src[i] = p + chunk * 8;
         dst_off[i] = (GA + gi) * GROUP_BYTES;
@@ -322,16 +322,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const bf16* __re
     const char* base = lds + stage * STAGE_BYTES;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[TM], fb[TN];
+      f16x8 fa[TM], fb[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(base + a_base[i] + koff[kk]);
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const f16x8*>(base + a_base[i] + koff[kk]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(base + b_base[j] + koff[kk]);
+      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const f16x8*>(base + b_base[j] + koff[kk]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
   };
 
@@ -360,7 +360,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const bf16* __re
   // (all remaining in-flight loads target LDS only; the epilogue does not touch LDS)
 
   if (MODE == GEMM_SWIGLU_BF16) {
-    bf16* C = reinterpret_cast<bf16*>(Cv);
+    f16* C = reinterpret_cast<f16*>(Cv);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const bf16* __re
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
           if (m < M && f < N)
-            C[(int64_t)m * ldc + f] = f2bf(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
+            C[(int64_t)m * ldc + f] = f2h(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
         }
       }
   } else {
@@ -397,7 +397,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const bf16* __re
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES, int MODE>
-hipError_t run_dma(hipStream_t s, const bf16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
+hipError_t run_dma(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
                    int splits) {
   if (K % BK) return hipErrorInvalidValue;
   constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_BF16 ? BN / 2 : BN;
@@ -414,7 +414,7 @@ hipError_t run_dma(hipStream_t s, const bf16* A, const GemmW& W, void* C, int M,
 }
 
 template <int BM, int BN, int WM, int WN, int MODE>
-hipError_t run(hipStream_t s, const bf16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
+hipError_t run(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
                int splits) {
   constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_BF16 ? BN / 2 : BN;
   const int n_tiles = (N + n_out_per_tile - 1) / n_out_per_tile, m_tiles = (M + BM - 1) / BM;
@@ -434,7 +434,7 @@ hipError_t run(hipStream_t s, const bf16* A, const GemmW& W, void* C, int M, int
 }
 
 template <int MODE>
-hipError_t dispatch(hipStream_t s, int cfg, const bf16* A, const GemmW& W, void* C, int M, int N, int K,
+hipError_t dispatch(hipStream_t s, int cfg, const f16* A, const GemmW& W, void* C, int M, int N, int K,
                     int ldc, int splits) {
   switch (cfg) {
     case 0: return run<128, 128, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
@@ -496,7 +496,7 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
   *splits = sp;
 }
 
-hipError_t launch_gemm_cfg(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
+hipError_t launch_gemm_cfg(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,
                            GemmMode mode, int cfg, int splits) {
   if (M <= 0 || N <= 0 || K <= 0 || K % 8 || ldc < N || !A || !C || !W.ptr[0]) return hipErrorInvalidValue;
   if (((uintptr_t)A | (uintptr_t)W.ptr[0] | (uintptr_t)W.ptr[1] | (uintptr_t)W.ptr[2]) & 15)
@@ -521,7 +521,7 @@ hipError_t launch_gemm_cfg(hipStream_t s, const bf16* A, GemmW W, void* C, int M
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_gemm(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
+hipError_t launch_gemm(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,
                        GemmMode mode) {
   // GEMM_STORE_F32 callers that did not zero C get no K split
   int cfg, splits;

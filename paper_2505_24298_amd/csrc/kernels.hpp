@@ -18,37 +18,37 @@ struct SeqState {              // device-resident per-sequence state
   int max_seq_len, max_blocks;
 };
 
-hipError_t launch_embed(hipStream_t s, const bf16* embed, int hidden, int vocab, int M, RowMeta rm,
+hipError_t launch_embed(hipStream_t s, const f16* embed, int hidden, int vocab, int M, RowMeta rm,
                         const int32_t* tokens_in, const int32_t* new_block, SeqState st, float* h);
 // zero_out (optional): float32 [M, zero_cols] cleared row by row alongside (the
 // buffer a following split-K product accumulates into).
-hipError_t launch_rmsnorm(hipStream_t s, const float* x, const bf16* gain, bf16* y, int M, int hidden,
+hipError_t launch_rmsnorm(hipStream_t s, const float* x, const f16* gain, f16* y, int M, int hidden,
                           float eps, const int32_t* src_rows, float* zero_out = nullptr,
                           int zero_cols = 0);
 hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
-                               const bf16* bq, const bf16* bk, const bf16* bv, const float* cos_tab,
-                               const float* sin_tab, bf16* q_out, bf16* arena_layer, KvGeom geom,
+                               const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
+                               const float* sin_tab, f16* q_out, f16* arena_layer, KvGeom geom,
                                int n_q_heads);
-hipError_t launch_f32_to_bf16(hipStream_t s, const float* src, bf16* dst, int64_t n);
+hipError_t launch_to_f16(hipStream_t s, const void* src, int src_is_bf16, f16* dst, int64_t n);
 
 // ---- gemm.hip ---------------------------------------------------------------
-// C[M,N] (+)= A[M,K] * W[N,K]^T, bf16 inputs, float32 accumulation on MFMA.
+// C[M,N] (+)= A[M,K] * W[N,K]^T, half-precision inputs, float32 accumulation on MFMA.
 // W may be up to three row-segments (e.g. wq | wk | wv), each [rows, K].
 struct GemmW {
-  const bf16* ptr[3];
+  const f16* ptr[3];
   int end[3];                  // cumulative row counts; end[last used] == N
 };
 enum GemmMode {
   GEMM_STORE_F32 = 0,          // C float32 = acc
   GEMM_ADD_F32 = 1,            // C float32 += acc            (residual update)
-  GEMM_SWIGLU_BF16 = 2,        // two W of [N,K] (gate, up): C bf16 = silu(A gate^T) * (A up^T)
+  GEMM_SWIGLU_BF16 = 2,        // two W of [N,K] (gate, up): C half = silu(A gate^T) * (A up^T)
 };
-hipError_t launch_gemm(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
+hipError_t launch_gemm(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,
                        GemmMode mode);
 // Same with an explicit tile configuration (0 .. gemm_num_configs()-1) and K
 // split; -1 = take the tuned choice.  A split > 1 accumulates with float32
 // atomics: for GEMM_STORE_F32 the caller must have zeroed C.
-hipError_t launch_gemm_cfg(hipStream_t s, const bf16* A, GemmW W, void* C, int M, int N, int K, int ldc,
+hipError_t launch_gemm_cfg(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,
                            GemmMode mode, int cfg, int splits);
 void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits);
 int gemm_num_configs();
@@ -60,12 +60,12 @@ struct AttnWork {              // prefill work item: 64 query rows of one sequen
 // decode: one query row per sequence (row i <-> rm.slot[i], rm.pos[i]); context
 // = pos+1 tokens.  `chunk` tokens per split (multiple of 64); partial results go
 // through `part_o` / `part_ml` when n_splits > 1.
-hipError_t launch_attn_decode(hipStream_t s, const bf16* q, int M, RowMeta rm, SeqState st,
-                              const bf16* arena_layer, KvGeom geom, int n_q_heads, int chunk,
-                              int n_splits, float* part_o, float* part_ml, bf16* out);
-hipError_t launch_attn_prefill(hipStream_t s, const bf16* q, const AttnWork* work, int n_work,
-                               SeqState st, const bf16* arena_layer, KvGeom geom, int n_q_heads,
-                               bf16* out);
+hipError_t launch_attn_decode(hipStream_t s, const f16* q, int M, RowMeta rm, SeqState st,
+                              const f16* arena_layer, KvGeom geom, int n_q_heads, int chunk,
+                              int n_splits, float* part_o, float* part_ml, f16* out);
+hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work, int n_work,
+                               SeqState st, const f16* arena_layer, KvGeom geom, int n_q_heads,
+                               f16* out);
 
 // ---- sampler.hip ------------------------------------------------------------
 hipError_t launch_sampler(hipStream_t s, int n, int vocab, const float* logits, const int32_t* seq_ids,

@@ -81,7 +81,7 @@ Layout make_layout(const areal_model_cfg& c) {
   const uint64_t per_pass = M * 16 + (M / 64 + 2 * (uint64_t)c.max_seqs + 64) * 16 + (uint64_t)c.max_seqs * 16;
   L.ring_bytes = align_up(std::max<uint64_t>(per_pass * 2, 1u << 20), 4096) * kRingSegs;
   L.ring = take(L.ring_bytes);
-  L.wconv_elems = c.fp32_weights ? total_params(c) : 0;
+  L.wconv_elems = c.convert_weights ? total_params(c) : 0;
   L.wconv = take(L.wconv_elems * 2);
   L.total = off;
   return L;
@@ -95,8 +95,8 @@ struct SeqInfo {
 };
 
 struct WeightSet {
-  const bf16 *embed = nullptr, *lm_head = nullptr, *final_norm = nullptr;
-  std::vector<const bf16*> wq, wk, wv, wo, wgate, wup, wdown, norm_attn, norm_ffn, bq, bk, bv;
+  const f16 *embed = nullptr, *lm_head = nullptr, *final_norm = nullptr;
+  std::vector<const f16*> wq, wk, wv, wo, wgate, wup, wdown, norm_attn, norm_ffn, bq, bk, bv;
   bool has_bias = false;
 };
 
@@ -192,8 +192,8 @@ bool weights_complete(const areal_ctx* c, const areal_weights* w) {
   return true;
 }
 
-// Install `w` as the current parameter set (bf16: borrow in place; f32: round
-// into the workspace copy, stream-ordered after all earlier passes).
+// Install `w` as the current parameter set (half: borrow in place; bf16 / f32:
+// convert into the workspace copy, stream-ordered after all earlier passes).
 int install_weights(areal_ctx* c, const areal_weights* w) {
   const areal_model_cfg& g = c->cfg;
   const int L = g.n_layers;
@@ -203,11 +203,11 @@ int install_weights(areal_ctx* c, const areal_weights* w) {
   ws.has_bias = w->bq != nullptr;
   uint64_t cursor = 0;
   hipError_t herr = hipSuccess;
-  auto get = [&](const void* p, uint64_t n) -> const bf16* {
-    if (w->dtype == AREAL_DTYPE_BF16) return reinterpret_cast<const bf16*>(p);
-    bf16* dst = c->wsp<bf16>(c->lay.wconv) + cursor;
+  auto get = [&](const void* p, uint64_t n) -> const f16* {
+    if (w->dtype == AREAL_DTYPE_F16) return reinterpret_cast<const f16*>(p);
+    f16* dst = c->wsp<f16>(c->lay.wconv) + cursor;
     cursor += align_up(n, 64);
-    if (herr == hipSuccess) herr = launch_f32_to_bf16(c->stream, reinterpret_cast<const float*>(p), dst, (int64_t)n);
+    if (herr == hipSuccess) herr = launch_to_f16(c->stream, p, w->dtype == AREAL_DTYPE_BF16, dst, (int64_t)n);
     return dst;
   };
   const bool tied = w->lm_head == w->embed;
@@ -238,9 +238,10 @@ int install_weights(areal_ctx* c, const areal_weights* w) {
 
 int check_weights_arg(areal_ctx* c, const areal_weights* w) {
   if (!weights_complete(c, w)) return fail(c, AREAL_E_INVAL, "incomplete weight set");
-  if (w->dtype != AREAL_DTYPE_BF16 && w->dtype != AREAL_DTYPE_F32) return fail(c, AREAL_E_INVAL, "unknown weight dtype");
-  if (w->dtype == AREAL_DTYPE_F32 && !c->cfg.fp32_weights)
-    return fail(c, AREAL_E_INVAL, "float32 weights need cfg.fp32_weights = 1 at creation");
+  if (w->dtype != AREAL_DTYPE_BF16 && w->dtype != AREAL_DTYPE_F32 && w->dtype != AREAL_DTYPE_F16)
+    return fail(c, AREAL_E_INVAL, "unknown weight dtype");
+  if (w->dtype != AREAL_DTYPE_F16 && !c->cfg.convert_weights)
+    return fail(c, AREAL_E_INVAL, "bf16 / float32 weights need cfg.convert_weights = 1 at creation");
   return AREAL_OK;
 }
 
@@ -290,15 +291,15 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
   hipStream_t s = c->stream;
   SeqState st = c->seq_state();
   float* h = c->wsp<float>(c->lay.h);
-  bf16* xn = c->wsp<bf16>(c->lay.xn);
+  f16* xn = c->wsp<f16>(c->lay.xn);
   float* qkv = c->wsp<float>(c->lay.qkv);
-  bf16* q = c->wsp<bf16>(c->lay.q);
-  bf16* attn = c->wsp<bf16>(c->lay.attn);
-  bf16* act = c->wsp<bf16>(c->lay.act);
-  bf16* xlast = c->wsp<bf16>(c->lay.xlast);
+  f16* q = c->wsp<f16>(c->lay.q);
+  f16* attn = c->wsp<f16>(c->lay.attn);
+  f16* act = c->wsp<f16>(c->lay.act);
+  f16* xlast = c->wsp<f16>(c->lay.xlast);
   const float* cos_t = c->wsp<float>(c->lay.cos_t);
   const float* sin_t = c->wsp<float>(c->lay.sin_t);
-  bf16* arena = reinterpret_cast<bf16*>(g.kv_arena);
+  f16* arena = reinterpret_cast<f16*>(g.kv_arena);
   const WeightSet& w = c->w;
 
   const bool sampled = c->prof_class >= 0 && (c->prof_pass++ % c->prof_every) == 0;
@@ -308,7 +309,7 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
     HIP_TRY(c, launch_embed(s, w.embed, H, g.vocab, a.M, a.rm, a.tokens_in, a.new_block, st, h));
   }
   for (int l = 0; l < g.n_layers; ++l) {
-    bf16* arena_l = arena + (int64_t)l * c->geom.layer_stride;
+    f16* arena_l = arena + (int64_t)l * c->geom.layer_stride;
     {
       ProfScope ps(c, AREAL_K_RMSNORM, l, sampled, rows);
       // the QKV product may split K and accumulate atomically: clear its output here
@@ -791,8 +792,8 @@ int areal_profile_end(areal_ctx* c, int64_t* n_out, double* ms_out, double* unit
 int areal_op_gemm(void* stream, const void* A, const void* W0, const void* W1, void* C, int32_t M,
                   int32_t N, int32_t K, int32_t mode, int32_t cfg, int32_t splits) {
   if (mode < 0 || mode > 2 || !A || !W0 || !C || (mode == 2 && !W1)) return AREAL_E_INVAL;
-  GemmW w{{(const bf16*)W0, mode == 2 ? (const bf16*)W1 : nullptr, nullptr}, {N, 0, 0}};
-  hipError_t e = launch_gemm_cfg((hipStream_t)stream, (const bf16*)A, w, C, M, N, K, N, (GemmMode)mode, cfg, splits);
+  GemmW w{{(const f16*)W0, mode == 2 ? (const f16*)W1 : nullptr, nullptr}, {N, 0, 0}};
+  hipError_t e = launch_gemm_cfg((hipStream_t)stream, (const f16*)A, w, C, M, N, K, N, (GemmMode)mode, cfg, splits);
   if (e == hipErrorInvalidValue) return AREAL_E_INVAL;
   return e == hipSuccess ? AREAL_OK : AREAL_E_HIP;
 }

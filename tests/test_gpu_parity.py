@@ -1,7 +1,7 @@
 """GPU parity: the HIP library (through the C ABI) against the CPU oracle on
 identical seeded inputs.  Tolerances are the ones the build is held to:
-logits max-abs error <= 2e-2, per-token log-prob error <= 1e-2 (bf16 weights,
-bf16 K/V, float32 accumulation); sampled token ids bit-exact given identical
+logits max-abs error <= 2e-2, per-token log-prob error <= 1e-2 (half-precision
+matrix operands and K/V, float32 accumulation); sampled token ids bit-exact given identical
 float32 logits and seed."""
 import numpy as np
 import pytest
@@ -28,12 +28,17 @@ def binding():
     return binding
 
 
-def _bf16_weights(w):
-    """The values the GPU computes with: every matrix rounded to bf16."""
-    out = dict(embed=synth.bf16_round(w["embed"]), lm_head=synth.bf16_round(w["lm_head"]),
-               final_norm=synth.bf16_round(w["final_norm"]), layers=[])
+def _f16(a):
+    return np.asarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+def _f16_weights(w):
+    """The values the GPU computes with: float32 parameters rounded to half
+    precision (nearest even), as the library does when it receives them."""
+    out = dict(embed=_f16(w["embed"]), lm_head=_f16(w["lm_head"]), final_norm=_f16(w["final_norm"]),
+               layers=[])
     for lw in w["layers"]:
-        out["layers"].append({k: synth.bf16_round(v) for k, v in lw.items()})
+        out["layers"].append({k: _f16(v) for k, v in lw.items()})
     return out
 
 
@@ -44,12 +49,12 @@ def _teacher_forced_run(torch, binding, cfg, w_f32, prompts, n_new, *, qkv_bias=
     logits and log-prob deviations.  `interrupt` = (step, new fp32 weights)."""
     from oracle import rollout
     ids = list(range(len(prompts))) if shuffle_ids is None else list(shuffle_ids)
-    wk = rollout.RolloutWorker(cfg, _bf16_weights(w_f32), version=0, seed=seed,
+    wk = rollout.RolloutWorker(cfg, _f16_weights(w_f32), version=0, seed=seed,
                                temperature=temperature, top_p=top_p)
     for s, p in zip(ids, prompts):
         wk.add(s, p)
     eng = binding.Areal(cfg, max_seqs=max(ids) + 1, max_seq_len=max(len(p) for p in prompts) + n_new + 1,
-                        max_batch_tokens=max_batch_tokens, kv_blocks=kv_blocks, fp32_weights=True)
+                        max_batch_tokens=max_batch_tokens, kv_blocks=kv_blocks, convert_weights=True)
     eng.load_weights(binding.weights_to_device(w_f32, bf16=False), 0)
     logits = eng.prefill(ids, prompts)
     worst_logit, worst_lb, worst_lf = 0.0, 0.0, 0.0
@@ -57,7 +62,7 @@ def _teacher_forced_run(torch, binding, cfg, w_f32, prompts, n_new, *, qkv_bias=
     for step in range(n_new):
         if interrupt is not None and step == interrupt[0]:
             version += 1
-            wk.update_weights(_bf16_weights(interrupt[1]), version)
+            wk.update_weights(_f16_weights(interrupt[1]), version)
             live, logits, retok = eng.update_weights_interrupt(
                 binding.weights_to_device(interrupt[1], bf16=False), version)
             assert live.tolist() == sorted(ids)
@@ -138,7 +143,7 @@ def test_top_p_temperature_teacher_forced(torch, binding):
 def test_errors_leave_state_unchanged(torch, binding):
     cfg = synth.shape("tiny")
     eng = binding.Areal(cfg, max_seqs=4, max_seq_len=64, max_batch_tokens=32, kv_blocks=3,
-                        fp32_weights=True)
+                        convert_weights=True)
     p = [np.arange(20, dtype=np.int32)]
     with pytest.raises(binding.ArealError) as e:
         eng.prefill([0], p)

@@ -44,10 +44,15 @@ def test_cfg_struct_matches_header_layout():
 
 
 def test_workspace_and_block_bytes(L):
-    cfg = binding.make_cfg(synth.shape("qwen2-1.5b"), 256, 8704, 8192)
+    cfg = binding.make_cfg(synth.shape("qwen2-1.5b"), 256, 8704, 8192, convert_weights=False)
     assert L.areal_kv_block_bytes(C.byref(cfg)) == 16 * 28672
     ws = L.areal_workspace_bytes(C.byref(cfg))
     assert 2 ** 20 < ws < 2 ** 31
+    # space for a converted half-precision copy of a bf16 / float32 parameter set
+    cfg_c = binding.make_cfg(synth.shape("qwen2-1.5b"), 256, 8704, 8192, convert_weights=True)
+    extra = L.areal_workspace_bytes(C.byref(cfg_c)) - ws
+    n_params = 1_543_656_960 + 151936 * 1536 + 28 * 1536      # + embedding, + second norm gain
+    assert 2 * n_params <= extra <= 2 * n_params + 2 ** 20
     cfg7 = binding.make_cfg(synth.shape("qwen2-7b"), 64, 33792 + 16, 4096)
     assert L.areal_kv_block_bytes(C.byref(cfg7)) == 16 * 57344
     bad = binding.make_cfg(synth.shape("tiny", head_dim=48), 8, 128, 64)
