@@ -122,6 +122,43 @@ __device__ __forceinline__ void attend_group(const KvFrag<D>& f, const f16x8 (&q
 }
 
 // ------------------------------------------------------------------ decode
+// Block ids of a split, fetched once: lane l of every wave holds the ids of
+// blocks b0 + l and b0 + 64 + l (a split spans at most 128 blocks).
+struct BlockIds { int lo, hi; };
+__device__ __forceinline__ int block_id(const BlockIds& t, int rel) {
+  const int v = rel < 64 ? t.lo : t.hi;
+  return __shfl(v, rel & 63);
+}
+
+template <int D>
+__device__ __forceinline__ void load_group_ids(KvFrag<D>& f, const f16* __restrict__ arena,
+                                               const KvGeom& geom, const BlockIds& ids, int b0, int b,
+                                               int b_end, int kvh, int lane) {
+  const int g = lane >> 4, j = lane & 15;
+  const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int u = 0; u < NB; ++u) {
+    if (b + u < b_end) {                               // wave-uniform
+      const int blk = block_id(ids, b + u - b0);
+      const f16* kt = arena + kv_tile_off(geom, blk, kvh, 0) + j * D + g * (D / 4);
+      const f16* vt = arena + kv_tile_off(geom, blk, kvh, 1) + lane * (D / 4);
+#pragma unroll
+      for (int c = 0; c < D / 32; ++c) {
+        f.k[u][c] = ld8(kt + c * 8);
+        f.v[u][c] = ld8(vt + c * 8);
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < D / 32; ++c) {
+        f.k[u][c] = zero8;
+        f.v[u][c] = zero8;
+      }
+    }
+  }
+}
+
+// One work-group per (split, kv head, sequence); the partials of a sequence cut
+// into several splits are combined by attn_merge_kernel.
 template <int D>
 __global__ __launch_bounds__(256) void attn_decode_kernel(
     const f16* __restrict__ q, RowMeta rm, SeqState st, const f16* __restrict__ arena, KvGeom geom,
@@ -139,6 +176,9 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   const int g = lane >> 4, j = lane & 15;
   const int G = nq / geom.n_kv_heads;
   const int32_t* table = st.table + (int64_t)rm.slot[i] * st.max_blocks;
+  BlockIds ids;
+  ids.lo = b0 + lane < b1 ? table[b0 + lane] : 0;
+  ids.hi = b0 + 64 + lane < b1 ? table[b0 + 64 + lane] : 0;
 
   f16x8 qf[D / 32];
   {
@@ -155,10 +195,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   // wave w takes block groups w, w+4, ... of this split
   int b = b0 + wave * NB;
   KvFrag<D> cur, nxt;
-  if (b < b1) load_group<D>(cur, arena, geom, table, b, b1, kvh, lane);
+  if (b < b1) load_group_ids<D>(cur, arena, geom, ids, b0, b, b1, kvh, lane);
   while (b < b1) {
     const int bn = b + 4 * NB;
-    if (bn < b1) load_group<D>(nxt, arena, geom, table, bn, b1, kvh, lane);
+    if (bn < b1) load_group_ids<D>(nxt, arena, geom, ids, b0, bn, b1, kvh, lane);
     attend_group<D>(cur, qf, b, pos, scale_log2, m, l, o, lane);
     cur = nxt;
     b = bn;
@@ -284,7 +324,7 @@ hipError_t launch_attn_decode(hipStream_t s, const f16* q, int M, RowMeta rm, Se
                               const f16* arena_layer, KvGeom geom, int n_q_heads, int chunk,
                               int n_splits, float* part_o, float* part_ml, f16* out) {
   if (M <= 0 || !geom_ok(geom, n_q_heads) || chunk <= 0 || chunk % (4 * NB * kBlockTokens) ||
-      n_splits <= 0 || (n_splits > 1 && (!part_o || !part_ml)))
+      chunk > 128 * kBlockTokens || n_splits <= 0 || (n_splits > 1 && (!part_o || !part_ml)))
     return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)geom.head_dim);
   dim3 grid(n_splits, geom.n_kv_heads, M);

@@ -21,7 +21,7 @@ constexpr int LDS_K = BK + 8;   // row stride in elements (144 B): conflict-free
 // null when it lies outside the matrix.
 template <int BN, int MODE>
 __device__ __forceinline__ const f16* w_row_ptr(const GemmW& W, int tile_n, int b, int N, int K) {
-  if (MODE == GEMM_SWIGLU_BF16) {
+  if (MODE == GEMM_SWIGLU_F16) {
     // every 64 tile rows = 32 gate rows then 32 up rows of the same 32 features
     const int grp = b >> 6, within = b & 63;
     const int isup = within >> 5, c = within & 31;
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const f16* __restric
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
   constexpr int ACH = BM * 8 / NT, BCH = BN * 8 / NT;   // 16-B chunks per thread per slab
   static_assert(TM >= 1 && TN >= 1 && ACH >= 1 && BCH >= 1, "tile too small for the wave grid");
-  static_assert(MODE != GEMM_SWIGLU_BF16 || (TN % 2 == 0), "SwiGLU needs gate+up in one wave tile");
+  static_assert(MODE != GEMM_SWIGLU_F16 || (TN % 2 == 0), "SwiGLU needs gate+up in one wave tile");
   __shared__ __attribute__((aligned(16))) f16 sA[2][BM * LDS_K];
   __shared__ __attribute__((aligned(16))) f16 sB[2][BN * LDS_K];
 
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const f16* __restric
   }
 
   // D layout of the 32x32 tile: lane (fh, fr) holds column fr, rows 8*(v/4) + 4*fh + v%4.
-  if (MODE == GEMM_SWIGLU_BF16) {
+  if (MODE == GEMM_SWIGLU_F16) {
     f16* C = reinterpret_cast<f16*>(Cv);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
   constexpr int GA = BM / 8, GB = BN / 8;              // row groups per slab
   constexpr int LPS = (GA + GB) / NW;                  // load instructions per wave per slab
   static_assert((GA + GB) % NW == 0 && GA % NW == 0, "row groups must divide over the waves");
-  static_assert(MODE != GEMM_SWIGLU_BF16 || (TN % 2 == 0), "SwiGLU needs gate+up in one wave tile");
+  static_assert(MODE != GEMM_SWIGLU_F16 || (TN % 2 == 0), "SwiGLU needs gate+up in one wave tile");
   constexpr int STAGE_BYTES = (GA + GB) * GROUP_BYTES;
   __shared__ __attribute__((aligned(16))) char lds[STAGES * STAGE_BYTES];
 
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
   }
   // (all remaining in-flight loads target LDS only; the epilogue does not touch LDS)
 
-  if (MODE == GEMM_SWIGLU_BF16) {
+  if (MODE == GEMM_SWIGLU_F16) {
     f16* C = reinterpret_cast<f16*>(Cv);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -400,7 +400,7 @@ template <int BM, int BN, int WM, int WN, int STAGES, int MODE>
 hipError_t run_dma(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
                    int splits) {
   if (K % BK) return hipErrorInvalidValue;
-  constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_BF16 ? BN / 2 : BN;
+  constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_F16 ? BN / 2 : BN;
   const int n_tiles = (N + n_out_per_tile - 1) / n_out_per_tile, m_tiles = (M + BM - 1) / BM;
   const int nk = K / BK;
   splits = std::max(1, std::min(splits, nk));
@@ -416,7 +416,7 @@ hipError_t run_dma(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, 
 template <int BM, int BN, int WM, int WN, int MODE>
 hipError_t run(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
                int splits) {
-  constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_BF16 ? BN / 2 : BN;
+  constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_F16 ? BN / 2 : BN;
   const int n_tiles = (N + n_out_per_tile - 1) / n_out_per_tile, m_tiles = (M + BM - 1) / BM;
   const int nk = (K + BK - 1) / BK;
   splits = std::max(1, std::min(splits, nk));
@@ -467,7 +467,7 @@ int gemm_num_configs() { return 16; }
 // (`cfg` / `splits` >= 0 in launch_gemm_cfg override them).
 void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
   const bool dma_ok = (K % BK) == 0;
-  const int n_tiles = mode == GEMM_SWIGLU_BF16 ? (N + 63) / 64 : (N + 127) / 128;
+  const int n_tiles = mode == GEMM_SWIGLU_F16 ? (N + 63) / 64 : (N + 127) / 128;
   const int nk = (K + BK - 1) / BK;
   int c, bm;
   if (!dma_ok) {                       // register-staged path (ragged K)
@@ -487,7 +487,7 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     else { c = 7; bm = 128; }
   }
   int sp = 1;
-  if (mode != GEMM_SWIGLU_BF16 && M <= 256) {
+  if (mode != GEMM_SWIGLU_F16 && M <= 256) {
     const int tiles = n_tiles * ((M + bm - 1) / bm);
     sp = (224 + tiles / 2) / std::max(tiles, 1);           // ~one work-group per compute unit
     sp = std::max(1, std::min(sp, std::max(1, nk / 3)));   // at least 3 slabs per split
@@ -514,9 +514,9 @@ hipError_t launch_gemm_cfg(hipStream_t s, const f16* A, GemmW W, void* C, int M,
     case GEMM_ADD_F32:
       if (W.end[0] != N) return hipErrorInvalidValue;
       return dispatch<GEMM_ADD_F32>(s, cfg, A, W, C, M, N, K, ldc, splits);
-    case GEMM_SWIGLU_BF16:
+    case GEMM_SWIGLU_F16:
       if (!W.ptr[1]) return hipErrorInvalidValue;
-      return dispatch<GEMM_SWIGLU_BF16>(s, cfg, A, W, C, M, N, K, ldc, 1);
+      return dispatch<GEMM_SWIGLU_F16>(s, cfg, A, W, C, M, N, K, ldc, 1);
   }
   return hipErrorInvalidValue;
 }

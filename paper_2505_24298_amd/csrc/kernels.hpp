@@ -41,7 +41,7 @@ struct GemmW {
 enum GemmMode {
   GEMM_STORE_F32 = 0,          // C float32 = acc
   GEMM_ADD_F32 = 1,            // C float32 += acc            (residual update)
-  GEMM_SWIGLU_BF16 = 2,        // two W of [N,K] (gate, up): C half = silu(A gate^T) * (A up^T)
+  GEMM_SWIGLU_F16 = 2,        // two W of [N,K] (gate, up): C half = silu(A gate^T) * (A up^T)
 };
 hipError_t launch_gemm(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,
                        GemmMode mode);
@@ -58,8 +58,8 @@ struct AttnWork {              // prefill work item: 64 query rows of one sequen
   int32_t slot, row0, pos0, n_rows;
 };
 // decode: one query row per sequence (row i <-> rm.slot[i], rm.pos[i]); context
-// = pos+1 tokens.  `chunk` tokens per split (multiple of 64); partial results go
-// through `part_o` / `part_ml` when n_splits > 1.
+// = pos+1 tokens.  `chunk` tokens per split (multiple of 128, at most 2048);
+// with n_splits > 1 the partials go through `part_o` / `part_ml` and a merge kernel.
 hipError_t launch_attn_decode(hipStream_t s, const f16* q, int M, RowMeta rm, SeqState st,
                               const f16* arena_layer, KvGeom geom, int n_q_heads, int chunk,
                               int n_splits, float* part_o, float* part_ml, f16* out);

@@ -46,6 +46,7 @@ bool cfg_valid(const areal_model_cfg* c, std::string* why) {
   if ((int64_t)c->vocab > 262144) return bad("vocab above 262144");
   if (c->max_seqs <= 0 || c->max_seq_len <= 0 || c->max_batch_tokens < c->max_seqs)
     return bad("need max_seqs > 0, max_seq_len > 0, max_batch_tokens >= max_seqs");
+  if (c->max_seq_len > kMaxSplits * 2048) return bad("max_seq_len above 65536");
   if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return bad("bad rope_theta / rms_eps");
   return true;
 }
@@ -343,7 +344,7 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
     {
       ProfScope ps(c, AREAL_K_GEMM_GATEUP, l, sampled, rows);
       GemmW wgu{{w.wgate[l], w.wup[l], nullptr}, {F, 0, 0}};
-      HIP_TRY(c, launch_gemm_cfg(s, xn, wgu, act, a.M, F, H, F, GEMM_SWIGLU_BF16, -1, -1));
+      HIP_TRY(c, launch_gemm_cfg(s, xn, wgu, act, a.M, F, H, F, GEMM_SWIGLU_F16, -1, -1));
     }
     {
       ProfScope ps(c, AREAL_K_GEMM_DOWN, l, sampled, rows);
@@ -611,7 +612,7 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
   if (rc) return rc;
   // split the KV walk so that the grid holds a few work-groups per compute unit
   int64_t chunk = (sum_ctx * g.n_kv_heads / 2048 + 127) / 128 * 128;
-  chunk = std::max<int64_t>(chunk, 256);
+  chunk = std::min<int64_t>(std::max<int64_t>(chunk, 256), 2048);   // a split spans at most 128 blocks
   int n_splits = (int)((max_ctx + chunk - 1) / chunk);
   if (n_splits > kMaxSplits) {
     chunk = ((max_ctx + kMaxSplits - 1) / kMaxSplits + 127) / 128 * 128;

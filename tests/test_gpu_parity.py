@@ -130,6 +130,18 @@ def test_tiny_interrupt_matches_fresh_prefill_under_new_weights(torch, binding):
     assert dl <= LOGIT_TOL and dlb <= LOGP_TOL and dlf <= LOGP_TOL
 
 
+def test_tiny_long_context_split_kv_decode(torch, binding):
+    """Contexts of several hundred tokens: decode attention is cut into KV splits
+    that are combined inside the kernel; prefill runs in several passes."""
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 2)
+    prompts = synth.make_prompts(cfg, 3, 1, 300, 700, seed=9)
+    dl, dlb, dlf = _teacher_forced_run(torch, binding, cfg, w, prompts, 6, max_batch_tokens=256,
+                                       kv_blocks=160)
+    print(f"tiny/long: logits {dl:.2e}  logp_behav {dlb:.2e}  logp_full {dlf:.2e}")
+    assert dl <= LOGIT_TOL and dlb <= LOGP_TOL and dlf <= LOGP_TOL
+
+
 def test_top_p_temperature_teacher_forced(torch, binding):
     cfg = synth.shape("tiny")
     w = synth.make_weights(cfg, 8)
