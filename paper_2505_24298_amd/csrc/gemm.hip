@@ -36,6 +36,31 @@ __device__ __forceinline__ const f16* w_row_ptr(const GemmW& W, int tile_n, int 
   }
 }
 
+// Block id -> (row tile, column tile, K split).  Work-groups are handed to the 8
+// XCDs round-robin, so ids equal mod 8 share one L2.  Inside an XCD consecutive
+// work-groups walk super-tiles of up to 8 row tiles x 4 column tiles (column
+// tile = 8*g + xcd): the 32 work-groups resident on an XCD's 32 compute units
+// then share each A slab 4 ways and each W slab 8 ways in that L2.
+constexpr int SUPER_M = 8, SUPER_N = 4;
+__host__ __device__ __forceinline__ int super_m(int m_tiles) { return m_tiles < SUPER_M ? m_tiles : SUPER_M; }
+__host__ __device__ __forceinline__ int grid_blocks(int m_tiles, int n_tiles, int splits) {
+  const int sm = super_m(m_tiles), n_groups = (n_tiles + 7) / 8;
+  const int mb = (m_tiles + sm - 1) / sm, nb = (n_groups + SUPER_N - 1) / SUPER_N;
+  return 8 * splits * nb * mb * sm * SUPER_N;
+}
+__device__ __forceinline__ bool tile_of_block(int id, int m_tiles, int n_tiles, int& tile_m, int& tile_n,
+                                              int& split) {
+  const int xcd = id & 7, q = id >> 3;
+  const int sm = super_m(m_tiles), n_groups = (n_tiles + 7) >> 3;
+  const int mb = (m_tiles + sm - 1) / sm, nb = (n_groups + SUPER_N - 1) / SUPER_N;
+  const int within = q % (sm * SUPER_N), sq = q / (sm * SUPER_N);
+  const int m_blk = sq % mb, rest = sq / mb;
+  tile_m = m_blk * sm + within % sm;
+  tile_n = ((rest % nb) * SUPER_N + within / sm) * 8 + xcd;
+  split = rest / nb;
+  return tile_m < m_tiles && tile_n < n_tiles;
+}
+
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
 template <int BM, int BN, int WM, int WN, int MODE, bool RAGGED_K>
@@ -53,13 +78,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const f16* __restric
 
   // block id -> (row tile, column tile, K split): ids that differ by a multiple
   // of 8 sit on the same XCD; the row tiles of one weight panel are adjacent there.
-  const int id = blockIdx.x, xcd = id & 7, grp = id >> 3;
-  const int tile_m = grp % m_tiles;
-  const int rest = grp / m_tiles;
-  const int n_groups = (n_tiles + 7) >> 3;
-  const int tile_n = (rest % n_groups) * 8 + xcd;
-  const int split = rest / n_groups;
-  if (tile_n >= n_tiles) return;
+  int tile_m, tile_n, split;
+  if (!tile_of_block(blockIdx.x, m_tiles, n_tiles, tile_m, tile_n, split)) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
@@ -253,13 +273,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
   constexpr int STAGE_BYTES = (GA + GB) * GROUP_BYTES;
   __shared__ __attribute__((aligned(16))) char lds[STAGES * STAGE_BYTES];
 
-  const int id = blockIdx.x, xcd = id & 7, grp = id >> 3;
-  const int tile_m = grp % m_tiles;
-  const int rest = grp / m_tiles;
-  const int n_groups = (n_tiles + 7) >> 3;
-  const int tile_n = (rest % n_groups) * 8 + xcd;
-  const int split = rest / n_groups;
-  if (tile_n >= n_tiles) return;
+  int tile_m, tile_n, split;
+  if (!tile_of_block(blockIdx.x, m_tiles, n_tiles, tile_m, tile_n, split)) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
@@ -318,21 +333,39 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
 #pragma unroll
   for (int kk = 0; kk < BK / 16; ++kk) koff[kk] = ((kk * 2 + fh) ^ (fr & 7)) << 4;
 
+  // Fragment reads run one K-step ahead of the MFMAs that consume them, so the
+  // LDS latency is covered by a full K-step of matrix work.
+  struct Frags { f16x8 a[TM], b[TN]; };
+  auto read_frags = [&](Frags& f, const char* base, int kk) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) f.a[i] = *reinterpret_cast<const f16x8*>(base + a_base[i] + koff[kk]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const f16x8*>(base + b_base[j] + koff[kk]);
+  };
+  auto mma = [&](const Frags& f) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+  };
   auto compute = [&](int stage) {
     const char* base = lds + stage * STAGE_BYTES;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      f16x8 fa[TM], fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const f16x8*>(base + a_base[i] + koff[kk]);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const f16x8*>(base + b_base[j] + koff[kk]);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
+    Frags f0, f1;
+    read_frags(f0, base, 0);
+    read_frags(f1, base, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f0, base, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(f1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f1, base, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(f1);
   };
 
   const int nk_all = K / BK;
@@ -406,8 +439,7 @@ hipError_t run_dma(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, 
   splits = std::max(1, std::min(splits, nk));
   const int sps = (nk + splits - 1) / splits;
   splits = (nk + sps - 1) / sps;
-  const int n_groups = (n_tiles + 7) / 8;
-  const int grid = m_tiles * n_groups * 8 * splits;
+  const int grid = grid_blocks(m_tiles, n_tiles, splits);
   gemm_dma_kernel<BM, BN, WM, WN, STAGES, MODE><<<grid, WM * WN * 64, 0, s>>>(
       A, W, C, M, N, K, ldc, m_tiles, n_tiles, sps, splits > 1 ? 1 : 0);
   return hipGetLastError();
@@ -422,8 +454,7 @@ hipError_t run(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, int 
   splits = std::max(1, std::min(splits, nk));
   const int sps = (nk + splits - 1) / splits;
   splits = (nk + sps - 1) / sps;
-  const int n_groups = (n_tiles + 7) / 8;
-  const int grid = m_tiles * n_groups * 8 * splits;
+  const int grid = grid_blocks(m_tiles, n_tiles, splits);
   if (K % BK)
     gemm_kernel<BM, BN, WM, WN, MODE, true><<<grid, WM * WN * 64, 0, s>>>(A, W, C, M, N, K, ldc, m_tiles,
                                                                           n_tiles, sps, splits > 1 ? 1 : 0);
@@ -454,13 +485,15 @@ hipError_t dispatch(hipStream_t s, int cfg, const f16* A, const GemmW& W, void* 
     case 13: return run_dma<128, 64, 2, 1, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 14: return run_dma<256, 64, 4, 1, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 15: return run_dma<128, 128, 2, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 16: return run_dma<256, 256, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 17: return run_dma<256, 128, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
     default: return hipErrorInvalidValue;
   }
 }
 
 }  // namespace
 
-int gemm_num_configs() { return 16; }
+int gemm_num_configs() { return 18; }
 
 // Tile configuration and K split for a product of this shape: rules read off
 // sweeps over every configuration on the MI355X at the decoder's shapes
@@ -475,7 +508,11 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     else if (M <= 64) { c = 2; bm = 64; }
     else { c = 0; bm = 128; }
   } else if (M > 256) {                // prefill: MFMA-bound, large tiles
-    c = 0; bm = 128;
+    const int t256 = (mode == GEMM_SWIGLU_F16 ? (N + 127) / 128 : (N + 255) / 256) * ((M + 255) / 256);
+    if (t256 >= 224) { *cfg = 16; *splits = 1; return; }
+    if (mode == GEMM_ADD_F32 && K >= 4096) { *cfg = 16; *splits = 2; return; }
+    *cfg = 8; *splits = 1;
+    return;
   } else if (n_tiles >= 100) {         // wide outputs: one work-group per column panel
     if (M <= 32) { c = 12; bm = 32; }
     else if (M <= 64) { c = 10; bm = 64; }
