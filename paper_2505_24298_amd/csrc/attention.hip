@@ -255,58 +255,202 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(const float* __restrict__
 }
 
 // ----------------------------------------------------------------- prefill
+// One work-group per (tile of 16 or 32 query positions, kv head): its rows are
+// those positions x the G query heads that share the kv head, cut into
+// row-groups of 16 (positions of one head), RGW row-groups per wave.  KV blocks
+// travel HBM -> LDS once per work-group (global_load_lds, a ring of PF_STAGES
+// stages of two blocks each) and every wave multiplies all its row-groups
+// against them, so each K/V byte fetched serves up to 32*G query rows.
+// Both products use the 16x16x32 MFMA: for P.V the 32-deep contraction runs
+// over the two blocks of a stage (slots 0-3: tokens 4g..4g+3 of the first
+// block, slots 4-7: of the second), which is the order the S^T accumulators and
+// the stored V tiles already have.
+constexpr int PF_STAGES = 3;
+
 template <int D>
+struct PairFrag {
+  f16x8 k[2][D / 32];
+  f16x8 v[2][D / 32];
+};
+
+template <int D>
+__device__ __forceinline__ void attend_pair(const PairFrag<D>& f, const f16x8 (&qf)[D / 32], int b,
+                                            int row_pos, float scale_log2, float& m, float& l,
+                                            f32x4 (&o)[D / 16], int lane) {
+  const int g = lane >> 4;
+  float s[2][4];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c) acc = mfma_qk(f.k[u][c], qf[c], acc);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int t = (b + u) * kBlockTokens + 4 * g + v;
+      s[u][v] = t <= row_pos ? acc[v] * scale_log2 : -INFINITY;
+      mx = fmaxf(mx, s[u][v]);
+    }
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m, mx);
+  const float m_use = m_new == -INFINITY ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+  m = m_new;
+  float psum = 0.f;
+  f16x8 p;
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float e = __builtin_amdgcn_exp2f(s[u][v] - m_use);
+      psum += e;
+      p[u * 4 + v] = f2h(e);
+    }
+  l = l * alpha + psum;
+  float ao[4];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) ao[v] = __shfl(alpha, 4 * g + v);
+#pragma unroll
+  for (int n = 0; n < D / 16; ++n) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) o[n][v] *= ao[v];
+    const f16x8 v0 = f.v[0][n >> 1], v1 = f.v[1][n >> 1];
+    f16x8 vb;
+    if (n & 1) vb = f16x8{v0[4], v0[5], v0[6], v0[7], v1[4], v1[5], v1[6], v1[7]};
+    else vb = f16x8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+    o[n] = mfma_qk(p, vb, o[n]);
+  }
+}
+
+template <int D, int RGW>
 __global__ __launch_bounds__(256) void attn_prefill_kernel(
     const f16* __restrict__ q, const AttnWork* __restrict__ work, SeqState st,
-    const f16* __restrict__ arena, KvGeom geom, int nq, float scale_log2, f16* __restrict__ out) {
+    const f16* __restrict__ arena, KvGeom geom, int nq, int tile_pos, float scale_log2,
+    f16* __restrict__ out) {
+  constexpr int CPR = D / 8;              // 16-byte chunks per K row
+  constexpr int NCH = D / 32;             // 16-byte chunks per lane of a V tile
+  constexpr int TILE_B = 16 * D * 2;      // bytes of one K or V tile
+  constexpr int STAGE_B = 4 * TILE_B;     // two blocks x (K, V)
+  constexpr int NI = TILE_B / 1024;       // load instructions per tile = per wave per stage
+  __shared__ __attribute__((aligned(16))) char lds[PF_STAGES * STAGE_B];
+
   const AttnWork wk = work[blockIdx.x];
-  const int head = blockIdx.y, kvh = head / (nq / geom.n_kv_heads);
+  const int kvh = blockIdx.y;
+  const int G = nq / geom.n_kv_heads;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, j = lane & 15;
-  const int r_first = wave * 16;
-  if (r_first >= wk.n_rows) return;
-  const int my_r = r_first + j;                       // row within the work item
-  const bool row_ok = my_r < wk.n_rows;
-  const int my_pos = wk.pos0 + my_r;                  // absolute position of this lane's row
-  const int last_pos = wk.pos0 + min(wk.n_rows, r_first + 16) - 1;
-  const int b1 = last_pos / kBlockTokens + 1;
+  const int n_rg = (tile_pos / 16) * G;
+  const int last_pos = wk.pos0 + wk.n_rows - 1;
+  const int b_end = last_pos / kBlockTokens + 1;
+  const int n_pairs = (b_end + 1) >> 1;
   const int32_t* table = st.table + (int64_t)wk.slot * st.max_blocks;
 
-  f16x8 qf[D / 32];
-  {
+  // ---- this wave's row-groups ----
+  f16x8 qf[RGW][D / 32];
+  float m[RGW], l[RGW];
+  f32x4 o[RGW][D / 16];
+  int rpos[RGW], gmax[RGW];
+#pragma unroll
+  for (int r = 0; r < RGW; ++r) {
+    const int rg = wave * RGW + r;
+    const int pos_blk = rg / G, head = kvh * G + rg % G;
+    const int row_in = pos_blk * 16 + j;
+    const bool active = rg < n_rg && pos_blk * 16 < wk.n_rows;
+    const bool ok = active && row_in < wk.n_rows;
+    gmax[r] = active ? wk.pos0 + min(wk.n_rows, pos_blk * 16 + 16) - 1 : -1;
+    rpos[r] = ok ? wk.pos0 + row_in : gmax[r];
     const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const f16* qp = q + ((int64_t)(wk.row0 + my_r) * nq + head) * D + g * (D / 4);
+    const f16* qp = q + ((int64_t)(wk.row0 + (ok ? row_in : 0)) * nq + (active ? head : 0)) * D + g * (D / 4);
 #pragma unroll
-    for (int c = 0; c < D / 32; ++c) qf[c] = row_ok ? ld8(qp + c * 8) : zero8;
+    for (int c = 0; c < D / 32; ++c) qf[r][c] = ok ? ld8(qp + c * 8) : zero8;
+    m[r] = -INFINITY;
+    l[r] = 0.f;
+#pragma unroll
+    for (int n = 0; n < D / 16; ++n) o[r][n] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  float m = -INFINITY, l = 0.f;
-  f32x4 o[D / 16];
-#pragma unroll
-  for (int n = 0; n < D / 16; ++n) o[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  int b = 0;
-  KvFrag<D> cur, nxt;
-  load_group<D>(cur, arena, geom, table, b, b1, kvh, lane);
-  while (b < b1) {
-    const int bn = b + NB;
-    if (bn < b1) load_group<D>(nxt, arena, geom, table, bn, b1, kvh, lane);
-    attend_group<D>(cur, qf, b, row_ok ? my_pos : last_pos, scale_log2, m, l, o, lane);
-    cur = nxt;
-    b = bn;
+  // ---- this wave's share of the loads: one tile of the stage (block u, K or V) ----
+  const int u_ld = wave >> 1, isv_ld = wave & 1;
+  int src_off[NI];
+#pragma unroll
+  for (int t = 0; t < NI; ++t) {
+    const int slot = t * 64 + lane;
+    if (!isv_ld) {                                   // K: slot (row, chunk ^ row) <- chunk of that row
+      const int row = slot / CPR, c = (slot % CPR) ^ (row & (CPR - 1));
+      src_off[t] = row * D + c * 8;
+    } else {                                         // V: slot (lane, i ^ f(lane)) <- chunk i of that lane
+      const int ln = slot / NCH, i = (slot % NCH) ^ ((ln >> 2) & (NCH - 1));
+      src_off[t] = (ln * NCH + i) * 8;
+    }
   }
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
-  float lo[4];
+  int id_chunk = -1, ids = 0;
+  auto issue = [&](int pair, int stage) {
+    const int b = min(2 * pair + u_ld, b_end - 1);     // past the end: re-read the last block (masked anyway)
+    if ((b >> 6) != id_chunk) {                        // wave-uniform
+      id_chunk = b >> 6;
+      const int bb = id_chunk * 64 + lane;
+      ids = bb < b_end ? table[bb] : 0;
+    }
+    const int blk = __shfl(ids, b & 63);
+    const f16* tile = arena + kv_tile_off(geom, blk, kvh, isv_ld);
+    char* dst = lds + stage * STAGE_B + (u_ld * 2 + isv_ld) * TILE_B;
 #pragma unroll
-  for (int v = 0; v < 4; ++v) lo[v] = __shfl(l, 4 * g + v);
+    for (int t = 0; t < NI; ++t) dma16(tile + src_off[t], dst + t * 1024);
+  };
+
+  // ---- fragment addresses inside a stage ----
+  int k_off[D / 32], v_off[D / 32];
 #pragma unroll
-  for (int v = 0; v < 4; ++v) {
-    const int r = r_first + 4 * g + v;
-    if (r < wk.n_rows) {
-      f16* op = out + ((int64_t)(wk.row0 + r) * nq + head) * D;
-      const float inv = 1.0f / lo[v];
+  for (int c = 0; c < D / 32; ++c) {
+    const int cc = g * NCH + c;
+    k_off[c] = (j * CPR + (cc ^ (j & (CPR - 1)))) * 16;
+    v_off[c] = (lane * NCH + (c ^ ((lane >> 2) & (NCH - 1)))) * 16;
+  }
+
 #pragma unroll
-      for (int n = 0; n < D / 16; ++n) op[16 * n + j] = f2h(o[n][v] * inv);
+  for (int s = 0; s < PF_STAGES - 1; ++s) issue(min(s, n_pairs - 1), s);
+  for (int p = 0; p < n_pairs; ++p) {
+    wait_vmcnt((PF_STAGES - 2) * NI);
+    __builtin_amdgcn_s_barrier();
+    issue(min(p + PF_STAGES - 1, n_pairs - 1), (p + PF_STAGES - 1) % PF_STAGES);
+    const char* base = lds + (p % PF_STAGES) * STAGE_B;
+    PairFrag<D> f;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int c = 0; c < D / 32; ++c) {
+        f.k[u][c] = *reinterpret_cast<const f16x8*>(base + (u * 2) * TILE_B + k_off[c]);
+        f.v[u][c] = *reinterpret_cast<const f16x8*>(base + (u * 2 + 1) * TILE_B + v_off[c]);
+      }
+#pragma unroll
+    for (int r = 0; r < RGW; ++r)
+      if (gmax[r] >= 2 * p * kBlockTokens)             // wave-uniform: the row-group sees this pair
+        attend_pair<D>(f, qf[r], 2 * p, rpos[r], scale_log2, m[r], l[r], o[r], lane);
+  }
+  wait_vmcnt(0);
+
+#pragma unroll
+  for (int r = 0; r < RGW; ++r) {
+    const int rg = wave * RGW + r;
+    const int pos_blk = rg / G, head = kvh * G + rg % G;
+    float lr = l[r];
+    lr += __shfl_xor(lr, 16);
+    lr += __shfl_xor(lr, 32);
+    float lo[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) lo[v] = __shfl(lr, 4 * g + v);
+    if (gmax[r] < 0) continue;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int row_in = pos_blk * 16 + 4 * g + v;
+      if (row_in < wk.n_rows) {
+        f16* op = out + ((int64_t)(wk.row0 + row_in) * nq + head) * D;
+        const float inv = 1.0f / lo[v];
+#pragma unroll
+        for (int n = 0; n < D / 16; ++n) op[16 * n + j] = f2h(o[r][n][v] * inv);
+      }
     }
   }
 }
@@ -343,17 +487,36 @@ hipError_t launch_attn_decode(hipStream_t s, const f16* q, int M, RowMeta rm, Se
   return hipGetLastError();
 }
 
+int attn_prefill_tile_rows(int n_q_heads, int n_kv_heads) {
+  return n_q_heads / n_kv_heads <= 8 ? 32 : 16;
+}
+
 hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work, int n_work,
                                SeqState st, const f16* arena_layer, KvGeom geom, int n_q_heads,
                                f16* out) {
   if (n_work <= 0 || !geom_ok(geom, n_q_heads)) return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)geom.head_dim);
-  dim3 grid(n_work, n_q_heads);
-  switch (geom.head_dim) {
-    case 32: attn_prefill_kernel<32><<<grid, 256, 0, s>>>(q, work, st, arena_layer, geom, n_q_heads, scale_log2, out); break;
-    case 64: attn_prefill_kernel<64><<<grid, 256, 0, s>>>(q, work, st, arena_layer, geom, n_q_heads, scale_log2, out); break;
-    default: attn_prefill_kernel<128><<<grid, 256, 0, s>>>(q, work, st, arena_layer, geom, n_q_heads, scale_log2, out); break;
+  const int G = n_q_heads / geom.n_kv_heads;
+  const int tile = attn_prefill_tile_rows(n_q_heads, geom.n_kv_heads);
+  const int rgw = ((tile / 16) * G + 3) / 4;           // row-groups per wave: 1 .. 4
+  dim3 grid(n_work, geom.n_kv_heads);
+#define AREAL_PF(DD, RR)                                                                          \
+  attn_prefill_kernel<DD, RR><<<grid, 256, 0, s>>>(q, work, st, arena_layer, geom, n_q_heads, tile, \
+                                                   scale_log2, out)
+#define AREAL_PF_D(DD)                                                                            \
+  switch (rgw) {                                                                                  \
+    case 1: AREAL_PF(DD, 1); break;                                                               \
+    case 2: AREAL_PF(DD, 2); break;                                                               \
+    case 3: AREAL_PF(DD, 3); break;                                                               \
+    default: AREAL_PF(DD, 4); break;                                                              \
   }
+  switch (geom.head_dim) {
+    case 32: AREAL_PF_D(32) break;
+    case 64: AREAL_PF_D(64) break;
+    default: AREAL_PF_D(128) break;
+  }
+#undef AREAL_PF_D
+#undef AREAL_PF
   return hipGetLastError();
 }
 

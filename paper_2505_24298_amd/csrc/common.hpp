@@ -37,6 +37,26 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// 16 bytes per lane, HBM -> LDS: lane i of the wave writes dst_wave_base + i*16.
+__device__ __forceinline__ void dma16(const void* src, void* dst_wave_base) {
+  __builtin_amdgcn_global_load_lds(
+      (const __attribute__((address_space(1))) void*)src,
+      (__attribute__((address_space(3))) void*)dst_wave_base, 16, 0, 0);
+}
+
+__device__ __forceinline__ void wait_vmcnt(int n) {
+  // s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt = [15:14]:[3:0])
+  switch (n) {
+#define AREAL_W(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | 0x0F70); break;
+    AREAL_W(0) AREAL_W(1) AREAL_W(2) AREAL_W(3) AREAL_W(4) AREAL_W(5) AREAL_W(6) AREAL_W(7) AREAL_W(8)
+    AREAL_W(9) AREAL_W(10) AREAL_W(11) AREAL_W(12) AREAL_W(13) AREAL_W(14) AREAL_W(15) AREAL_W(16)
+    AREAL_W(18) AREAL_W(20) AREAL_W(21) AREAL_W(24) AREAL_W(27) AREAL_W(28) AREAL_W(30) AREAL_W(32)
+    AREAL_W(36) AREAL_W(40) AREAL_W(48)
+#undef AREAL_W
+    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+  }
+}
+
 // ---- paged KV arena addressing --------------------------------------------
 // arena = [layer][block][kv_head][K tile | V tile], tiles of 16*d halves.
 //   K tile: [token 0..15][d]                       (row-major)

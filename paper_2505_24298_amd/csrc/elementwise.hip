@@ -44,45 +44,58 @@ hipError_t launch_embed(hipStream_t s, const f16* embed, int hidden, int vocab, 
   return hipGetLastError();
 }
 
-// y = x / sqrt(mean(x^2) + eps) * gain, one wavefront per row, f16 out.
-// src_rows (optional) gathers: output row r is computed from input row src_rows[r].
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x,
-                                                      const f16* __restrict__ gain,
-                                                      f16* __restrict__ y, int M, int H, float eps,
-                                                      const int32_t* __restrict__ src_rows,
-                                                      float* __restrict__ zero_out, int zero_cols) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= M) return;
+// y = x / sqrt(mean(x^2) + eps) * gain: one single-wave work-group per row (so
+// that a decode batch spreads over all compute units), the row held in
+// registers between the reduction and the scaling.  src_rows (optional)
+// gathers: output row r is computed from input row src_rows[r].
+template <int NV>   // float4 vectors per lane: hidden <= NV * 256
+__global__ __launch_bounds__(64) void rmsnorm_kernel(const float* __restrict__ x,
+                                                     const f16* __restrict__ gain, f16* __restrict__ y,
+                                                     int H, float eps, const int32_t* __restrict__ src_rows,
+                                                     float* __restrict__ zero_out, int zero_cols) {
+  const int lane = threadIdx.x, row = blockIdx.x;
   const int src = src_rows ? src_rows[row] : row;
   const float* xp = x + (int64_t)src * H;
+  f32x4 v[NV];
   float ss = 0.f;
-  for (int c = lane * 4; c < H; c += 256) {
-    f32x4 v = *reinterpret_cast<const f32x4*>(xp + c);
-    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-  }
-  ss = wave_sum(ss);
-  const float r = 1.0f / sqrtf(ss / (float)H + eps);
-  f16* yp = y + (int64_t)row * H;
-  for (int c = lane * 4; c < H; c += 256) {
-    f32x4 v = *reinterpret_cast<const f32x4*>(xp + c);
-    f16x4 g = *reinterpret_cast<const f16x4*>(gain + c);
-    f16x4 o;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = f2h(v[i] * r * h2f(g[i]));
-    *reinterpret_cast<f16x4*>(yp + c) = o;
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    v[i] = c < H ? *reinterpret_cast<const f32x4*>(xp + c) : f32x4{0.f, 0.f, 0.f, 0.f};
+    ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
   }
   if (zero_out) {
     float* zp = zero_out + (int64_t)row * zero_cols;
     const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
     for (int c = lane * 4; c < zero_cols; c += 256) *reinterpret_cast<f32x4*>(zp + c) = z4;
   }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)H + eps);
+  f16* yp = y + (int64_t)row * H;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < H) {
+      const f16x4 g = *reinterpret_cast<const f16x4*>(gain + c);
+      f16x4 o;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = f2h(v[i][k] * r * h2f(g[k]));
+      *reinterpret_cast<f16x4*>(yp + c) = o;
+    }
+  }
 }
 
 hipError_t launch_rmsnorm(hipStream_t s, const float* x, const f16* gain, f16* y, int M, int hidden,
                           float eps, const int32_t* src_rows, float* zero_out, int zero_cols) {
-  if (M <= 0 || hidden % 4 || (zero_out && zero_cols % 4)) return hipErrorInvalidValue;
-  rmsnorm_kernel<<<(M + 3) / 4, 256, 0, s>>>(x, gain, y, M, hidden, eps, src_rows, zero_out, zero_cols);
+  if (M <= 0 || hidden % 4 || hidden > 32 * 256 || (zero_out && zero_cols % 4)) return hipErrorInvalidValue;
+  if (hidden <= 2 * 256)
+    rmsnorm_kernel<2><<<M, 64, 0, s>>>(x, gain, y, hidden, eps, src_rows, zero_out, zero_cols);
+  else if (hidden <= 8 * 256)
+    rmsnorm_kernel<8><<<M, 64, 0, s>>>(x, gain, y, hidden, eps, src_rows, zero_out, zero_cols);
+  else if (hidden <= 16 * 256)
+    rmsnorm_kernel<16><<<M, 64, 0, s>>>(x, gain, y, hidden, eps, src_rows, zero_out, zero_cols);
+  else
+    rmsnorm_kernel<32><<<M, 64, 0, s>>>(x, gain, y, hidden, eps, src_rows, zero_out, zero_cols);
   return hipGetLastError();
 }
 

@@ -54,9 +54,10 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits);
 int gemm_num_configs();
 
 // ---- attention.hip ----------------------------------------------------------
-struct AttnWork {              // prefill work item: 64 query rows of one sequence
-  int32_t slot, row0, pos0, n_rows;
+struct AttnWork {              // prefill work item: a tile of consecutive query rows of one sequence
+  int32_t slot, row0, pos0, n_rows;   // n_rows <= attn_prefill_tile_rows()
 };
+int attn_prefill_tile_rows(int n_q_heads, int n_kv_heads);   // 16 or 32
 // decode: one query row per sequence (row i <-> rm.slot[i], rm.pos[i]); context
 // = pos+1 tokens.  `chunk` tokens per split (multiple of 128, at most 2048);
 // with n_splits > 1 the partials go through `part_o` / `part_ml` and a merge kernel.

@@ -43,6 +43,7 @@ bool cfg_valid(const areal_model_cfg* c, std::string* why) {
   if (c->n_q_heads % c->n_kv_heads || c->n_q_heads / c->n_kv_heads > 16)
     return bad("n_q_heads must be a multiple of n_kv_heads with at most 16 query heads per KV head");
   if (c->hidden % 8 || c->ffn % 8) return bad("hidden and ffn must be multiples of 8");
+  if (c->hidden > 8192) return bad("hidden above 8192");
   if ((int64_t)c->vocab > 262144) return bad("vocab above 262144");
   if (c->max_seqs <= 0 || c->max_seq_len <= 0 || c->max_batch_tokens < c->max_seqs)
     return bad("need max_seqs > 0, max_seq_len > 0, max_batch_tokens >= max_seqs");
@@ -79,7 +80,7 @@ Layout make_layout(const areal_model_cfg& c) {
   L.cos_t = take((uint64_t)c.max_seq_len * (d / 2) * 4);
   L.sin_t = take((uint64_t)c.max_seq_len * (d / 2) * 4);
   // per pass: slot, pos, token, new_block per row + work items + last rows
-  const uint64_t per_pass = M * 16 + (M / 64 + 2 * (uint64_t)c.max_seqs + 64) * 16 + (uint64_t)c.max_seqs * 16;
+  const uint64_t per_pass = M * 16 + (M / 16 + 2 * (uint64_t)c.max_seqs + 64) * 16 + (uint64_t)c.max_seqs * 16;
   L.ring_bytes = align_up(std::max<uint64_t>(per_pass * 2, 1u << 20), 4096) * kRingSegs;
   L.ring = take(L.ring_bytes);
   L.wconv_elems = c.convert_weights ? total_params(c) : 0;
@@ -367,6 +368,7 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
               const std::vector<int64_t>& tok_offset, bool install_blocks, float* logits_out) {
   const areal_model_cfg& g = c->cfg;
   auto passes = plan_passes(spans, g.max_batch_tokens);
+  const int tile_rows = attn_prefill_tile_rows(g.n_q_heads, g.n_kv_heads);
   // span index lookup for token offsets: pieces come in span order
   size_t span_i = 0;
   int done_in_span = 0;
@@ -374,7 +376,7 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
     int M = 0, n_work = 0, n_out = 0;
     for (auto& p : pass) {
       M += p.len;
-      n_work += (p.len + 63) / 64;
+      n_work += (p.len + tile_rows - 1) / tile_rows;
       if (p.out_index >= 0) ++n_out;
     }
     const uint64_t bytes = align_up((uint64_t)M * 4, 64) * 4 + align_up((uint64_t)n_work * sizeof(AttnWork), 64) +
@@ -401,7 +403,8 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
         if (tokens) htok[p.row0 + r] = tokens[tok_offset[span_i] + done_in_span + r];
         hnb[p.row0 + r] = (install_blocks && pos % AREAL_KV_BLOCK_TOKENS == 0) ? blocks[pos / AREAL_KV_BLOCK_TOKENS] : -1;
       }
-      for (int r = 0; r < p.len; r += 64) hwork[wi++] = AttnWork{p.slot, p.row0 + r, p.pos0 + r, std::min(64, p.len - r)};
+      for (int r = 0; r < p.len; r += tile_rows)
+        hwork[wi++] = AttnWork{p.slot, p.row0 + r, p.pos0 + r, std::min(tile_rows, p.len - r)};
       done_in_span += p.len;
       if (p.out_index >= 0) {
         if (first_out < 0) first_out = p.out_index;
