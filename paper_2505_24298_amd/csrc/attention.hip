@@ -309,13 +309,19 @@ __device__ __forceinline__ void attend_pair(const PairFrag<D>& f, const f16x8 (&
       p[u * 4 + v] = f2h(e);
     }
   l = l * alpha + psum;
-  float ao[4];
+  // the running maximum settles after a few blocks: rescale the accumulator only
+  // when some row of the wave actually moved (wave-uniform branch)
+  if (__any(alpha != 1.0f)) {
+    float ao[4];
 #pragma unroll
-  for (int v = 0; v < 4; ++v) ao[v] = __shfl(alpha, 4 * g + v);
+    for (int v = 0; v < 4; ++v) ao[v] = __shfl(alpha, 4 * g + v);
+#pragma unroll
+    for (int n = 0; n < D / 16; ++n)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) o[n][v] *= ao[v];
+  }
 #pragma unroll
   for (int n = 0; n < D / 16; ++n) {
-#pragma unroll
-    for (int v = 0; v < 4; ++v) o[n][v] *= ao[v];
     const f16x8 v0 = f.v[0][n >> 1], v1 = f.v[1][n >> 1];
     f16x8 vb;
     if (n & 1) vb = f16x8{v0[4], v0[5], v0[6], v0[7], v1[4], v1[5], v1[6], v1[7]};
