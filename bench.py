@@ -194,6 +194,54 @@ def cpu_oracle_baseline(cfg_name, budget_s=20.0):
                        f"{t_prefill:.1f} s and is not in the rate)")
 
 
+def depth_sweep(args):
+    """Decode-step time against context depth for the deep-context workload
+    (64 sequences of the 7B shape, T=0.6, top-p=0.95): the paged pool is taken
+    as already holding `depth` tokens per sequence (areal_adopt_seq: no
+    generation up to that depth), then --sweep-steps decode steps are timed.
+    Prints one JSON line per depth; not the headline benchmark."""
+    import torch
+    from paper_2505_24298_amd import binding, synth
+    cfg, wl, _, _ = synth.make_workload(args.workload)
+    n = wl["n_prompts"] * wl["samples"]
+    depths = [int(x) for x in args.depth_sweep.split(",")]
+    steps = args.sweep_steps
+    w0 = device_weights(torch, cfg, 0, "cuda:0")
+    for depth in depths:
+        eng = binding.Areal(cfg, max_seqs=n, max_seq_len=depth + steps + 8, max_batch_tokens=max(n, 256),
+                            kv_blocks=n * ((depth + steps) // 16 + 2))
+        eng.load_weights(w0, 0)
+        eng.kv_arena.view(torch.float16).normal_()               # K/V contents: N(0,1) halves, not zeros
+        for s_ in range(n):
+            eng.adopt_seq(s_, depth, 1)
+        ids = np.arange(n, dtype=np.int32)
+        logits = torch.zeros((n, cfg["vocab"]), dtype=torch.float32, device="cuda:0")
+        out = (torch.ones(n, dtype=torch.int32, device="cuda:0"), torch.empty(n, device="cuda:0"),
+               torch.empty(n, device="cuda:0"))
+        eng.decode_step(ids, out[0], logits_out=logits)          # untimed first step
+        eng.profile_begin(binding.K_ATTN_DECODE, 0, 1)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        nbytes = 0.0
+        e0.record()
+        for t in range(steps):
+            eng.sample_logprob(logits, ids, np.full(n, depth + 1 + t), wl["temperature"], wl["top_p"], 0, out=out)
+            eng.decode_step(ids, out[0], logits_out=logits)
+            nbytes += decode_step_bytes(cfg, n * (depth + 2 + t), n)
+        e1.record()
+        cnt, ams, units = eng.profile_end()
+        ms = e0.elapsed_time(e1)
+        kvb = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * 2
+        print(json.dumps({"workload": args.workload, "sequences": n, "depth": depth, "decode_steps": steps,
+                          "ms_per_decode_step": round(ms / steps, 3), "gen_tokens_per_s": round(n * steps / ms * 1e3, 1),
+                          "hbm_GBps_algorithmic": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                          "hbm_frac_of_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                          "attn_decode_GBps": round(units * kvb / (ams * 1e-3) / 1e9, 1),
+                          "attn_decode_us": round(ams / cnt * 1e3, 1)}), flush=True)
+        eng.close()
+        del eng, logits, out
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -206,6 +254,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-class", type=int, default=4, help="kernel class bracketed with events")
     ap.add_argument("--profile-every", type=int, default=16)
+    ap.add_argument("--depth-sweep", default="", help="comma-separated context depths: time decode steps at "
+                    "each depth (deep-context workload) instead of the rollout")
+    ap.add_argument("--sweep-steps", type=int, default=32)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one MI355X: this build has no multi-GPU path (--gpus must be 1)",
@@ -215,6 +266,9 @@ def main():
     import torch
     from paper_2505_24298_amd import binding, synth
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    if args.depth_sweep:
+        depth_sweep(args)
+        return
     dev = "cuda:0"
     cfg, wl, prompts, out_lens = synth.make_workload(args.workload, scale_out=args.scale_out)
     n = len(prompts)

