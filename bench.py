@@ -101,7 +101,7 @@ def rollout(eng, torch, cfg, prompts, out_lens, temperature, top_p, seed, interr
     ev = lambda: torch.cuda.Event(enable_timing=True)
     e_start, e_prefill, e_end = ev(), ev(), ev()
     res = dict(prefill_tokens=int(plen.sum()), gen_tokens=int(out_lens.sum()), decode_steps=0,
-               decode_bytes=0.0, reprefill_tokens=0, interrupts=0, reprefill_ms=0.0)
+               decode_bytes=0.0, ctx_tokens=0, reprefill_tokens=0, interrupts=0, reprefill_ms=0.0)
     re_events = []
 
     torch.cuda.synchronize()
@@ -133,6 +133,7 @@ def rollout(eng, torch, cfg, prompts, out_lens, temperature, top_p, seed, interr
             a, b = ev(), ev()
             eng.decode_step(ids[:live], toks[:live], logits_out=logits[:live])
             res["decode_bytes"] += decode_step_bytes(cfg, int((plen[:live] + gen).sum()), live)
+            res["ctx_tokens"] += int((plen[:live] + gen).sum())
             res["decode_steps"] += 1
             version += 1
             a.record()
@@ -146,6 +147,7 @@ def rollout(eng, torch, cfg, prompts, out_lens, temperature, top_p, seed, interr
             continue
         eng.decode_step(ids[:live], toks[:live], logits_out=logits[:live])
         res["decode_bytes"] += decode_step_bytes(cfg, int((plen[:live] + gen).sum()), live)
+        res["ctx_tokens"] += int((plen[:live] + gen).sum())
         res["decode_steps"] += 1
     e_end.record()
     torch.cuda.synchronize()
@@ -252,7 +254,8 @@ def main():
     ap.add_argument("--interrupt-every", type=int, default=0)
     ap.add_argument("--max-batch-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-class", type=int, default=4, help="kernel class bracketed with events")
+    ap.add_argument("--profile-class", type=int, default=4,
+                    help="kernel class bracketed with HIP events (-1: none, e.g. under rocprofv3 --pmc)")
     ap.add_argument("--profile-every", type=int, default=16)
     ap.add_argument("--depth-sweep", default="", help="comma-separated context depths: time decode steps at "
                     "each depth (deep-context workload) instead of the rollout")
@@ -289,7 +292,7 @@ def main():
     runs = []
     for it in range(args.warmup + args.steps):
         eng.load_weights(w0, 0)
-        prof = (args.profile_class, 0, args.profile_every)
+        prof = (args.profile_class, 0, args.profile_every) if args.profile_class >= 0 else None
         r = rollout(eng, torch, cfg, prompts, out_lens, wl["temperature"], wl["top_p"], 0,
                     interrupt_every=args.interrupt_every, weight_sets=weight_sets, profile=prof)
         if it >= args.warmup:
@@ -299,7 +302,7 @@ def main():
     dec_ms = sum(r["decode_ms"] for r in runs)
     pre_ms = sum(r["prefill_ms"] for r in runs)
     dec_bytes = sum(r["decode_bytes"] for r in runs)
-    pn, pms, punits = (sum(r["profile"][i] for r in runs) for i in range(3))
+    pn, pms, punits = (sum(r["profile"][i] for r in runs) for i in range(3)) if "profile" in runs[0] else (0, 0.0, 0.0)
     kv_layer_bytes = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * 2          # K+V bytes per token per layer
     if args.profile_class == binding.K_ATTN_DECODE and pn:
         achieved = punits * kv_layer_bytes / (pms * 1e-3) / 1e9
@@ -325,7 +328,10 @@ def main():
         "decode": {"tokens_per_s": round(gen / (dec_ms * 1e-3), 1),
                    "hbm_GBps_algorithmic": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
                    "hbm_frac_of_peak": round(dec_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                   "ms_per_decode_step": round(dec_ms / max(1, sum(r["decode_steps"] for r in runs)), 4)},
+                   "ms_per_decode_step": round(dec_ms / max(1, sum(r["decode_steps"] for r in runs)), 4),
+                   "attn_decode_launches": cfg["n_layers"] * sum(r["decode_steps"] for r in runs),
+                   "attn_decode_kv_bytes_algorithmic": int(kv_layer_bytes * cfg["n_layers"]
+                                                           * sum(r["ctx_tokens"] for r in runs))},
         "prefill": {"tokens_per_s": round(sum(r["prefill_tokens"] for r in runs) / (pre_ms * 1e-3), 1),
                     "mfma_frac_of_peak": round(sum(r["prefill_flops"] for r in runs) / (pre_ms * 1e-3)
                                                / (MFMA_F16_PEAK_TFLOPS * 1e12), 4)},

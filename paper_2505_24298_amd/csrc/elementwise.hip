@@ -157,6 +157,24 @@ hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta r
   return hipGetLastError();
 }
 
+// Per-pass metadata travels from the pinned host ring to its device mirror in a
+// kernel of the library's own (16-byte words; src is device-mapped host memory).
+__global__ __launch_bounds__(256) void stage_copy_kernel(const u32x4* __restrict__ src,
+                                                         u32x4* __restrict__ dst, int n16) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+
+hipError_t launch_stage_copy(hipStream_t s, const void* src_host_mapped, void* dst, size_t bytes) {
+  if (!src_host_mapped || !dst || bytes == 0 || bytes % 16 || ((uintptr_t)src_host_mapped & 15) ||
+      ((uintptr_t)dst & 15) || bytes > (size_t)1 << 30)
+    return hipErrorInvalidValue;
+  const int n16 = (int)(bytes / 16);
+  stage_copy_kernel<<<(n16 + 255) / 256, 256, 0, s>>>(reinterpret_cast<const u32x4*>(src_host_mapped),
+                                                      reinterpret_cast<u32x4*>(dst), n16);
+  return hipGetLastError();
+}
+
 // Parameter sets arrive as float32 or bf16 and are held as halves for the
 // matrix cores (round to nearest even; bf16 values with |w| >= 2^-14 convert
 // exactly).  Magnitudes beyond the half range saturate to +-65504.

@@ -29,6 +29,7 @@ hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta r
                                const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                                const float* sin_tab, f16* q_out, f16* arena_layer, KvGeom geom,
                                int n_q_heads);
+hipError_t launch_stage_copy(hipStream_t s, const void* src_host_mapped, void* dst, size_t bytes);
 hipError_t launch_to_f16(hipStream_t s, const void* src, int src_is_bf16, f16* dst, int64_t n);
 
 // ---- gemm.hip ---------------------------------------------------------------

@@ -118,6 +118,7 @@ struct areal_ctx {
   int64_t version = 0;
   // metadata ring: pinned host mirror of a device ring, reused segment by segment
   char* ring_host = nullptr;
+  char* ring_host_dev = nullptr;        // the same pinned memory as the device addresses it
   uint64_t seg_bytes = 0, seg_used = 0;
   int seg = 0;
   hipEvent_t seg_done[kRingSegs];
@@ -174,7 +175,7 @@ int ring_flush(areal_ctx* c, uint64_t start_used) {
   const uint64_t off = (uint64_t)c->seg * c->seg_bytes + start_used;
   const uint64_t n = c->seg_used - start_used;
   if (n == 0) return AREAL_OK;
-  HIP_TRY(c, hipMemcpyAsync(c->ws + c->lay.ring + off, c->ring_host + off, n, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, launch_stage_copy(c->stream, c->ring_host_dev + off, c->ws + c->lay.ring + off, n));
   return AREAL_OK;
 }
 
@@ -480,8 +481,10 @@ int areal_create(const areal_model_cfg* cfg, areal_ctx** out) {
     areal_destroy(c);
     return fail(nullptr, AREAL_E_HIP, m);
   };
-  hipError_t e = hipHostMalloc((void**)&c->ring_host, lay.ring_bytes, hipHostMallocDefault);
+  hipError_t e = hipHostMalloc((void**)&c->ring_host, lay.ring_bytes, hipHostMallocMapped);
   if (e != hipSuccess) { c->ring_host = nullptr; return die(e, "hipHostMalloc(ring)"); }
+  e = hipHostGetDevicePointer((void**)&c->ring_host_dev, c->ring_host, 0);
+  if (e != hipSuccess) return die(e, "hipHostGetDevicePointer(ring)");
   for (int i = 0; i < kRingSegs; ++i) {
     e = hipEventCreateWithFlags(&c->seg_done[i], hipEventDisableTiming);
     if (e != hipSuccess) { c->seg_done[i] = nullptr; return die(e, "hipEventCreate"); }
@@ -751,8 +754,10 @@ int areal_adopt_seq(areal_ctx* c, int32_t id, int32_t len, int32_t fill_token) {
   c->alloc->reserve(id, len);
   Staged t = ring_take(c, nb * 4);
   memcpy(t.host, c->alloc->blocks(id).data(), nb * 4);
-  HIP_TRY(c, hipMemcpyAsync(c->wsp<int32_t>(c->lay.table) + (int64_t)id * c->lay.max_blocks, t.host, nb * 4,
-                            hipMemcpyHostToDevice, c->stream));
+  // table rows start on 16-byte boundaries only if max_blocks % 4 == 0: go through the device ring
+  HIP_TRY(c, launch_stage_copy(c->stream, c->ring_host_dev + (t.host - c->ring_host), t.dev, align_up(nb * 4, 16)));
+  HIP_TRY(c, hipMemcpyAsync(c->wsp<int32_t>(c->lay.table) + (int64_t)id * c->lay.max_blocks, t.dev, nb * 4,
+                            hipMemcpyDeviceToDevice, c->stream));
   HIP_TRY(c, hipMemsetD32Async((hipDeviceptr_t)(c->wsp<int32_t>(c->lay.hist) + (int64_t)id * g.max_seq_len),
                                fill_token, (size_t)len, c->stream));
   SeqInfo& s = c->seqs[id];

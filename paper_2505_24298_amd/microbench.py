@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Single-kernel microbenchmarks on the MI355X (tuning and profiling aids).
+
+  python3 paper_2505_24298_amd/microbench.py attn-decode
+      decode steps at the context mixes the qwen2-1.5b-rollout workload has after
+      500 / 1500 / 3000 / 5000 / 7000 generated tokens (sequences adopted at those
+      lengths, K/V pool filled with N(0,1)); reports the decode-attention launch
+      time and bandwidth (HIP events inside the library) and the step time.
+  python3 paper_2505_24298_amd/microbench.py gemm [M,M,...] [shape,...]
+      every tile configuration x K split of the projection GEMM at the decoder's
+      shapes (qkv, o, gateup, down, lmhead of the 1.5B shape); weights rotate over
+      > 1 GB so they come from HBM.
+  python3 paper_2505_24298_amd/microbench.py prefill
+      prefill of 32x256, 8x2048, 4x8000 tokens: per-kernel time of one layer.
+"""
+from __future__ import annotations
+
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+
+def _weights(torch, cfg):
+    from bench import device_weights
+    return device_weights(torch, cfg, 0, "cuda:0")
+
+
+def attn_decode():
+    import torch
+    from paper_2505_24298_amd import binding, synth
+    cfg, _, prompts, outs = synth.make_workload("qwen2-1.5b-rollout")
+    w = _weights(torch, cfg)
+    kvb = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * 2
+    for step in (500, 1500, 3000, 5000, 7000):
+        lens = [len(p) + step for p, o in zip(prompts, outs) if o > step]
+        B = len(lens)
+        eng = binding.Areal(cfg, max_seqs=B, max_seq_len=max(lens) + 64, max_batch_tokens=max(B, 256),
+                            kv_blocks=sum(l // 16 + 6 for l in lens))
+        eng.load_weights(w, 0)
+        eng.kv_arena.view(torch.float16).normal_()
+        for s, l in enumerate(lens):
+            eng.adopt_seq(s, l, 1)
+        ids = np.arange(B, dtype=np.int32)
+        toks = torch.ones(B, dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            eng.decode_step(ids, toks)
+        eng.profile_begin(binding.K_ATTN_DECODE, 0, 1)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = 12
+        e0.record()
+        for _ in range(n):
+            eng.decode_step(ids, toks)
+        e1.record()
+        cnt, ms, units = eng.profile_end()
+        print(json.dumps(dict(after_tokens=step, sequences=B, mean_context=int(np.mean(lens)),
+                              context_tokens_per_launch=int(units / cnt),
+                              attn_launch_us=round(ms / cnt * 1e3, 2),
+                              attn_GBps=round(units * kvb / (ms * 1e-3) / 1e9, 1),
+                              step_ms=round(e0.elapsed_time(e1) / n, 3))), flush=True)
+        eng.close()
+        del eng
+
+
+def gemm(ms_arg, shapes_arg):
+    import torch
+    from paper_2505_24298_amd import binding
+    L = binding.lib()
+    ncfg = L.areal_op_gemm_num_configs()
+    shapes = {"qkv": (2048, 1536, 0), "o": (1536, 1536, 1), "gateup": (8960, 1536, 2),
+              "down": (1536, 8960, 1), "lmhead": (151936, 1536, 0)}
+    Ms = [int(x) for x in ms_arg.split(",")]
+    g = torch.Generator(device="cuda").manual_seed(0)
+    for name in shapes_arg.split(","):
+        N, K, mode = shapes[name]
+        wbytes = N * K * 2 * (2 if mode == 2 else 1)
+        ncopy = max(2, min(64, int(1.2e9 // wbytes)))
+        mk = lambda: (torch.randn((N, K), generator=g, device="cuda") * 0.02).to(torch.float16)
+        Ws = [mk() for _ in range(ncopy)]
+        W1s = [mk() for _ in range(ncopy)] if mode == 2 else None
+        for M in Ms:
+            A = torch.randn((M, K), generator=g, device="cuda").to(torch.float16)
+            C = torch.zeros((M, N), device="cuda", dtype=torch.float16 if mode == 2 else torch.float32)
+            for cfg in range(ncfg):
+                for splits in ([1] if mode == 2 or name == "lmhead" else [1, 2, 4, 8, 16]):
+                    if cfg >= 7 and K % 64:
+                        continue
+                    iters = 3 * ncopy if wbytes < 1e8 else 6
+
+                    def run(n):
+                        for i in range(n):
+                            binding.op_gemm(A, Ws[i % ncopy], None if W1s is None else W1s[i % ncopy], C, mode,
+                                            cfg, splits)
+                    run(ncopy if wbytes < 1e8 else 2)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    run(iters)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    us = e0.elapsed_time(e1) * 1e3 / iters
+                    print(json.dumps(dict(shape=name, M=M, cfg=cfg, splits=splits, us=round(us, 2),
+                                          weight_GBps=round(wbytes / us / 1e3, 1),
+                                          TFLOPs=round(2.0 * M * N * K * (2 if mode == 2 else 1) / us / 1e6, 1))),
+                          flush=True)
+        del Ws, W1s
+
+
+def prefill():
+    import torch
+    from paper_2505_24298_amd import binding, synth
+    cfg = synth.shape("qwen2-1.5b")
+    w = _weights(torch, cfg)
+    classes = [(binding.K_ATTN_PREFILL, "attn"), (binding.K_GEMM_GATEUP, "gateup"), (binding.K_GEMM_DOWN, "down"),
+               (binding.K_GEMM_QKV, "qkv"), (binding.K_GEMM_O, "o")]
+    for n_seq, plen in [(32, 256), (8, 2048), (4, 8000)]:
+        eng = binding.Areal(cfg, max_seqs=n_seq, max_seq_len=plen + 8, max_batch_tokens=8192,
+                            kv_blocks=n_seq * (plen // 16 + 2))
+        eng.load_weights(w, 0)
+        prompts = synth.make_prompts(cfg, n_seq, 1, plen, plen, seed=3)
+        ids = list(range(n_seq))
+        eng.prefill(ids, prompts)                     # untimed: loads the code objects
+        for s in ids:
+            eng.free_seq(s)
+        res = dict(sequences=n_seq, prompt_len=plen)
+        for klass, nm in classes:
+            eng.profile_begin(klass, 0, 1)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            eng.prefill(ids, prompts)
+            e1.record()
+            cnt, ms, units = eng.profile_end()
+            res[nm + "_ms_layer0"] = round(ms, 3)
+            if nm == "attn":
+                res["attn_TFLOPs"] = round(units * 4 * cfg["n_q_heads"] * cfg["head_dim"] / (ms * 1e-3) / 1e12, 1)
+            total = e0.elapsed_time(e1)
+            for s in ids:
+                eng.free_seq(s)
+        res.update(total_ms=round(total, 1), tokens_per_s=round(n_seq * plen / total * 1e3))
+        print(json.dumps(res), flush=True)
+        eng.close()
+        del eng
+
+
+if __name__ == "__main__":
+    what = sys.argv[1] if len(sys.argv) > 1 else ""
+    if what == "attn-decode":
+        attn_decode()
+    elif what == "gemm":
+        gemm(sys.argv[2] if len(sys.argv) > 2 else "32,64,128,256",
+             sys.argv[3] if len(sys.argv) > 3 else "qkv,o,gateup,down,lmhead")
+    elif what == "prefill":
+        prefill()
+    else:
+        print(__doc__)
+        sys.exit(2)
