@@ -29,6 +29,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 / bf16
+# HBM bytes the decode attention kernel moves per algorithmic K/V byte, from rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs calibrated with a plain copy (profiles/attn_decode_kernel_hbm_traffic.md)
+ATTN_DECODE_FETCH_OVER_ALGORITHMIC = 1.014
+ATTN_DECODE_WRITE_OVER_ALGORITHMIC = 0.023
 
 
 def device_weights(torch, cfg, seed, device, base=None, scale=None):
@@ -306,9 +310,15 @@ def main():
     kv_layer_bytes = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * 2          # K+V bytes per token per layer
     if args.profile_class == binding.K_ATTN_DECODE and pn:
         achieved = punits * kv_layer_bytes / (pms * 1e-3) / 1e9
+        alg_per_launch = punits * kv_layer_bytes / pn
         roofline = dict(bound="hbm", kernel="attn_decode_kernel", achieved=round(achieved, 1),
                         peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
-                        traffic=None, launches_timed=int(pn), avg_launch_us=round(pms / pn * 1e3, 2),
+                        traffic=int(alg_per_launch * (ATTN_DECODE_FETCH_OVER_ALGORITHMIC
+                                                      + ATTN_DECODE_WRITE_OVER_ALGORITHMIC)),
+                        traffic_unit="bytes per launch (counter ratios of profiles/attn_decode_kernel_hbm_traffic.md"
+                                     " x this run's algorithmic bytes per launch)",
+                        algorithmic_bytes_per_launch=int(alg_per_launch),
+                        launches_timed=int(pn), avg_launch_us=round(pms / pn * 1e3, 2),
                         avg_context_tokens_per_launch=round(punits / pn, 1))
     else:
         roofline = dict(bound="hbm", kernel=f"class {args.profile_class}", achieved=None, peak=HBM_PEAK_GBS,
