@@ -119,7 +119,9 @@ int areal_load_weights(areal_ctx* ctx, const areal_weights* w, uint64_t version)
  *   seq_ids    host [n_seqs]   unused ids in 0 .. max_seqs-1, all distinct
  *   tokens     host [cu_seqlens[n_seqs]]  packed prompts, each length >= 1
  *   cu_seqlens host [n_seqs+1] prefix sums of the prompt lengths, [0] = 0
- *   logits_out device float32 [n_seqs, vocab] */
+ *   logits_out device float32 [n_seqs, vocab]
+ * n_seqs == 0 is a no-op (AREAL_OK, no pointer is read).  On any error no
+ * sequence is admitted and no block is reserved. */
 int areal_prefill(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
                   const int32_t* tokens, const int32_t* cu_seqlens, float* logits_out);
 
@@ -130,7 +132,9 @@ int areal_prefill(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
  *   tokens_in device int32 [n_seqs]  (typically tokens_out of the sampler)
  *   logits_out device float32 [n_seqs, vocab]  logits for the NEXT token
  * The appended token is tagged with the version whose logits it was sampled
- * from (the version loaded when those logits were computed). */
+ * from (the version loaded when those logits were computed).
+ * n_seqs == 0 is a no-op.  AREAL_E_NOMEM (KV pool exhausted, or a sequence at
+ * max_seq_len) leaves every sequence as it was: free some and call again. */
 int areal_decode_step(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
                       const int32_t* tokens_in, float* logits_out);
 
@@ -151,7 +155,7 @@ int areal_decode_step(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
  *                  tokens (-inf behaviour log-prob outside the nucleus).
  *   tokens_out device int32 [n]; logp_behav_out device float32 [n];
  *   logp_full_out device float32 [n] or NULL.
- * T <= 0, top_p <= 0 or NaN -> AREAL_E_INVAL. */
+ * T <= 0, top_p <= 0 or NaN -> AREAL_E_INVAL; n == 0 is a no-op. */
 int areal_sample_logprob(areal_ctx* ctx, int32_t n, const float* logits,
                          const int32_t* seq_ids, const int32_t* positions,
                          float temperature, float top_p, uint64_t philox_seed,

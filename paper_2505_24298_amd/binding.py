@@ -226,7 +226,8 @@ class Areal:
         ids, ids_p = _i32(seq_ids)
         cu = np.zeros(len(prompts) + 1, dtype=np.int32)
         cu[1:] = np.cumsum([len(p) for p in prompts])
-        toks, toks_p = _i32(np.concatenate([np.asarray(p, dtype=np.int32) for p in prompts]))
+        toks, toks_p = _i32(np.concatenate([np.asarray(p, dtype=np.int32) for p in prompts])
+                            if len(prompts) else np.zeros(0, dtype=np.int32))
         if logits_out is None:
             logits_out = torch.empty((len(ids), self.vocab), dtype=torch.float32, device=self.device)
         self._check(self.L.areal_prefill(self.ctx, len(ids), ids_p, toks_p, cu.ctypes.data_as(_I32P),

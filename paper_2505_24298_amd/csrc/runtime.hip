@@ -539,8 +539,10 @@ int areal_prefill(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t
                   const int32_t* cu, float* logits_out) {
   if (!c) return AREAL_E_INVAL;
   if (!c->have_weights) return fail(c, AREAL_E_STATE, "no weights loaded");
-  if (n <= 0 || !seq_ids || !tokens || !cu || !logits_out) return fail(c, AREAL_E_INVAL, "NULL or empty argument");
+  if (n == 0) return AREAL_OK;                       // nothing to admit
+  if (n < 0 || !seq_ids || !tokens || !cu || !logits_out) return fail(c, AREAL_E_INVAL, "NULL argument or negative count");
   const areal_model_cfg& g = c->cfg;
+  if (n > g.max_seqs) return fail(c, AREAL_E_INVAL, "more sequences than max_seqs");
   if (cu[0] != 0) return fail(c, AREAL_E_INVAL, "cu_seqlens[0] must be 0");
   std::vector<char> seen(g.max_seqs, 0);
   int64_t need_blocks = 0;
@@ -577,7 +579,8 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
                       float* logits_out) {
   if (!c) return AREAL_E_INVAL;
   if (!c->have_weights) return fail(c, AREAL_E_STATE, "no weights loaded");
-  if (n <= 0 || !seq_ids || !tokens_in || !logits_out) return fail(c, AREAL_E_INVAL, "NULL or empty argument");
+  if (n == 0) return AREAL_OK;                       // every sequence has finished
+  if (n < 0 || !seq_ids || !tokens_in || !logits_out) return fail(c, AREAL_E_INVAL, "NULL argument or negative count");
   const areal_model_cfg& g = c->cfg;
   if (n > g.max_seqs) return fail(c, AREAL_E_INVAL, "more rows than max_seqs");
   std::vector<char> seen(g.max_seqs, 0);
@@ -644,7 +647,8 @@ int areal_sample_logprob(areal_ctx* c, int32_t n, const float* logits, const int
                          const int32_t* positions, float temperature, float top_p, uint64_t seed,
                          const int32_t* forced, int32_t* tokens_out, float* logp_behav, float* logp_full) {
   if (!c) return AREAL_E_INVAL;
-  if (n <= 0 || !logits || !tokens_out || !logp_behav) return fail(c, AREAL_E_INVAL, "NULL or empty argument");
+  if (n == 0) return AREAL_OK;
+  if (n < 0 || !logits || !tokens_out || !logp_behav) return fail(c, AREAL_E_INVAL, "NULL argument or negative count");
   if (!(temperature > 0.f) || !(top_p > 0.f)) return fail(c, AREAL_E_INVAL, "temperature and top_p must be > 0");
   if (!forced && (!seq_ids || !positions)) return fail(c, AREAL_E_INVAL, "seq_ids and positions are required to draw");
   const int32_t *d_ids = nullptr, *d_pos = nullptr;

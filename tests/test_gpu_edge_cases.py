@@ -1,0 +1,237 @@
+"""GPU edge cases of the rollout path, each checked against the CPU oracle or
+against the state the library reports: empty calls, prompts of one token and at
+KV-block boundaries, ragged decode batches (a different subset of sequences
+each step), sequence ids reused after termination, KV-pool exhaustion and the
+max_seq_len limit during decode, and a weight update with nothing in flight."""
+import numpy as np
+import pytest
+
+from paper_2505_24298_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 2e-2
+LOGP_TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2505_24298_amd import binding
+    binding.lib()
+    return binding
+
+
+def _f16(a):
+    return np.asarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+def _f16_weights(w):
+    out = dict(embed=_f16(w["embed"]), lm_head=_f16(w["lm_head"]), final_norm=_f16(w["final_norm"]),
+               layers=[])
+    for lw in w["layers"]:
+        out["layers"].append({k: _f16(v) for k, v in lw.items()})
+    return out
+
+
+def _engine(binding, cfg, w, **kw):
+    args = dict(max_seqs=8, max_seq_len=96, max_batch_tokens=64, kv_blocks=64, convert_weights=True)
+    args.update(kw)
+    eng = binding.Areal(cfg, **args)
+    eng.load_weights(binding.weights_to_device(w, bf16=False), 0)
+    return eng
+
+
+def _oracle(cfg, w, seed=0):
+    from oracle import rollout
+    return rollout.RolloutWorker(cfg, _f16_weights(w), version=0, seed=seed)
+
+
+def _check_step(torch, eng, wk, ids, logits, seed=0):
+    """Compare the GPU logits for the next token of `ids` with the oracle's, let
+    the oracle draw, force its tokens on the GPU sampler; returns the tokens."""
+    positions = [len(wk.tokens[s]) for s in ids]
+    ref_logits, ref_tok = wk.step(ids)
+    got = logits.cpu().numpy()
+    assert np.abs(got - ref_logits).max() <= LOGIT_TOL
+    forced = torch.from_numpy(ref_tok).to(logits.device)
+    toks, lb, lf = eng.sample_logprob(logits, ids, positions, 1.0, 1.0, seed, forced_tokens=forced)
+    ref_lb = np.array([wk.logp_behav[s][-1] for s in ids])
+    assert np.abs(lb.cpu().numpy() - ref_lb).max() <= LOGP_TOL
+    return toks
+
+
+def test_empty_calls_are_noops(torch, binding):
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 0)
+    eng = _engine(binding, cfg, w)
+    before = eng.kv_blocks()
+    lg = eng.prefill([], [])
+    assert tuple(lg.shape) == (0, cfg["vocab"])
+    empty_tok = torch.zeros(0, dtype=torch.int32, device="cuda")
+    lg = eng.decode_step([], empty_tok)
+    assert tuple(lg.shape) == (0, cfg["vocab"])
+    t, lb, lf = eng.sample_logprob(torch.zeros((0, cfg["vocab"]), device="cuda"), [], [])
+    assert t.numel() == 0 and lb.numel() == 0
+    assert eng.kv_blocks() == before
+    # the context still works afterwards
+    wk = _oracle(cfg, w)
+    p = synth.make_prompts(cfg, 1, 1, 9, 9, seed=1)
+    wk.add(0, p[0])
+    _check_step(torch, eng, wk, [0], eng.prefill([0], p))
+    eng.close()
+
+
+def test_prompts_of_one_token_and_at_block_boundaries(torch, binding):
+    """Prompt lengths 1, 15, 16, 17, 31, 32, 33 (KV blocks hold 16 tokens); 20
+    generated tokens take every sequence across at least one block boundary."""
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 11)
+    lens = [1, 15, 16, 17, 31, 32, 33]
+    rng = np.random.default_rng(3)
+    prompts = [rng.integers(0, cfg["vocab"], size=n).astype(np.int32) for n in lens]
+    ids = list(range(len(lens)))
+    eng = _engine(binding, cfg, w, max_batch_tokens=48)
+    wk = _oracle(cfg, w)
+    for s, p in zip(ids, prompts):
+        wk.add(s, p)
+    logits = eng.prefill(ids, prompts)
+    for _ in range(20):
+        toks = _check_step(torch, eng, wk, ids, logits)
+        logits = eng.decode_step(ids, toks)
+    for s in ids:
+        assert eng.seq_len(s) == lens[s] + 20
+        assert eng.get_tokens(s).tolist() == wk.tokens[s]
+    total, free = eng.kv_blocks()
+    assert total - free == sum((n + 20 + 15) // 16 for n in lens)
+    eng.close()
+
+
+def test_ragged_decode_batches(torch, binding):
+    """Each step decodes a different subset of the live sequences, in a
+    different order: rows of a pass are independent of their position in it."""
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 12)
+    prompts = synth.make_prompts(cfg, 5, 1, 5, 40, seed=8)
+    ids = [4, 1, 3, 0, 2]
+    eng = _engine(binding, cfg, w)
+    wk = _oracle(cfg, w)
+    for s, p in zip(ids, prompts):
+        wk.add(s, p)
+    first = eng.prefill(ids, prompts)
+    # every sequence must take its first token from the prefill logits
+    toks = _check_step(torch, eng, wk, ids, first)
+    pending = {s: toks[i:i + 1] for i, s in enumerate(ids)}       # sampled, not yet appended
+    rng = np.random.default_rng(5)
+    for step in range(12):
+        k = int(rng.integers(1, len(ids) + 1))
+        subset = [int(s) for s in rng.permutation(ids)[:k]]
+        tok_in = torch.cat([pending[s] for s in subset])
+        logits = eng.decode_step(subset, tok_in)
+        toks = _check_step(torch, eng, wk, subset, logits)
+        for i, s in enumerate(subset):
+            pending[s] = toks[i:i + 1]
+    for s in ids:
+        assert eng.get_tokens(s).tolist() == wk.tokens[s][:-1]   # the last draw is still pending
+    eng.close()
+
+
+def test_sequence_id_reuse_after_termination(torch, binding):
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 13)
+    pa, pb = synth.make_prompts(cfg, 2, 1, 20, 40, seed=4)
+    eng = _engine(binding, cfg, w, max_seqs=2, kv_blocks=8)
+    wk = _oracle(cfg, w)
+    wk.add(0, pa)
+    logits = eng.prefill([0], [pa])
+    for _ in range(5):
+        toks = _check_step(torch, eng, wk, [0], logits)
+        logits = eng.decode_step([0], toks)
+    eng.free_seq(0)
+    assert eng.seq_len(0) == -1 and eng.kv_blocks() == (8, 8)
+    with pytest.raises(binding.ArealError) as e:
+        eng.decode_step([0], toks)                                # terminated
+    assert e.value.code == binding.E_STATE
+    wk2 = _oracle(cfg, w)
+    wk2.add(0, pb)
+    logits = eng.prefill([0], [pb])                               # same id, new prompt
+    for _ in range(5):
+        toks = _check_step(torch, eng, wk2, [0], logits)
+        logits = eng.decode_step([0], toks)
+    assert eng.get_tokens(0).tolist() == wk2.tokens[0]
+    v = eng.get_versions(0)
+    assert v.tolist() == [-1] * len(pb) + [0] * 5
+    eng.close()
+
+
+def test_kv_exhaustion_during_decode_leaves_state(torch, binding):
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 14)
+    rng = np.random.default_rng(6)
+    prompts = [rng.integers(0, cfg["vocab"], size=16).astype(np.int32) for _ in range(2)]
+    eng = _engine(binding, cfg, w, kv_blocks=3)                   # 2 blocks taken by the prompts
+    wk = _oracle(cfg, w)
+    for s, p in enumerate(prompts):
+        wk.add(s, p)
+    logits = eng.prefill([0, 1], prompts)
+    toks = _check_step(torch, eng, wk, [0, 1], logits)
+    with pytest.raises(binding.ArealError) as e:
+        eng.decode_step([0, 1], toks)                             # both need a second block, one is free
+    assert e.value.code == binding.E_NOMEM
+    assert eng.seq_len(0) == 16 and eng.seq_len(1) == 16 and eng.kv_blocks() == (3, 1)
+    eng.free_seq(1)
+    logits = eng.decode_step([0], toks[:1])                       # now it fits
+    assert eng.seq_len(0) == 17
+    wk.finish(1)
+    _check_step(torch, eng, wk, [0], logits)
+    eng.close()
+
+
+def test_max_seq_len_limit(torch, binding):
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 15)
+    p = synth.make_prompts(cfg, 1, 1, 30, 30, seed=2)
+    eng = _engine(binding, cfg, w, max_seq_len=32)
+    wk = _oracle(cfg, w)
+    wk.add(0, p[0])
+    with pytest.raises(binding.ArealError) as e:
+        eng.prefill([1], [np.zeros(33, dtype=np.int32)])          # longer than max_seq_len
+    assert e.value.code == binding.E_NOMEM and eng.seq_len(1) == -1
+    logits = eng.prefill([0], p)
+    for _ in range(2):                                            # positions 30 and 31: the last two
+        toks = _check_step(torch, eng, wk, [0], logits)
+        logits = eng.decode_step([0], toks)
+    assert eng.seq_len(0) == 32
+    toks = _check_step(torch, eng, wk, [0], logits)               # logits at full length are still right
+    with pytest.raises(binding.ArealError) as e:
+        eng.decode_step([0], toks)
+    assert e.value.code == binding.E_NOMEM and eng.seq_len(0) == 32
+    eng.close()
+
+
+def test_weight_update_with_nothing_in_flight(torch, binding):
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 16)
+    w2 = synth.perturb_weights(w, 1001, scale=5e-3, round_bf16=False)
+    eng = _engine(binding, cfg, w)
+    live, logits, retok = eng.update_weights_interrupt(binding.weights_to_device(w2, bf16=False), 7)
+    assert live.tolist() == [] and retok == 0
+    with pytest.raises(binding.ArealError) as e:                  # versions only go up
+        eng.update_weights_interrupt(binding.weights_to_device(w, bf16=False), 7)
+    assert e.value.code == binding.E_STATE
+    from oracle import rollout
+    wk = rollout.RolloutWorker(cfg, _f16_weights(w2), version=7, seed=0)
+    p = synth.make_prompts(cfg, 2, 1, 10, 20, seed=9)
+    for s in (0, 1):
+        wk.add(s, p[s])
+    logits = eng.prefill([0, 1], p)                               # runs under the new weights
+    toks = _check_step(torch, eng, wk, [0, 1], logits)
+    eng.decode_step([0, 1], toks)
+    assert eng.get_versions(0)[-1] == 7
+    eng.close()
