@@ -234,24 +234,38 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
 }
 
 // Combine the split partials of one (row, head): out = sum_s O_s 2^(M_s-M) / sum_s L_s 2^(M_s-M).
+// Lane s of each wave fetches (M_s, L_s), so the statistics cost one round trip
+// and two wave reductions; the O_s rows are then fetched four splits at a time.
 template <int D>
-__global__ __launch_bounds__(D) void attn_merge_kernel(const float* __restrict__ part_o,
+__global__ __launch_bounds__(D < 64 ? 64 : D) void attn_merge_kernel(const float* __restrict__ part_o,
                                                        const float* __restrict__ part_ml, RowMeta rm,
                                                        int nq, int chunk, int n_splits,
                                                        f16* __restrict__ out) {
   const int i = blockIdx.x / nq;
   const int ctx = rm.pos[i] + 1;
-  const int ns = min(n_splits, (ctx + chunk - 1) / chunk);
+  const int ns = min(n_splits, (ctx + chunk - 1) / chunk);   // <= 32 < lanes of a wave
   const int64_t base = (int64_t)blockIdx.x * n_splits;
-  float M = -INFINITY;
-  for (int s = 0; s < ns; ++s) M = fmaxf(M, part_ml[(base + s) * 2]);
-  float L = 0.f, O = 0.f;
-  for (int s = 0; s < ns; ++s) {
-    const float sc = __builtin_amdgcn_exp2f(part_ml[(base + s) * 2] - M);
-    L += part_ml[(base + s) * 2 + 1] * sc;
-    O += part_o[(base + s) * D + threadIdx.x] * sc;
+  const int lane = threadIdx.x & 63;
+  float ms = -INFINITY, ls = 0.f;
+  if (lane < ns) {
+    const float2 ml = *reinterpret_cast<const float2*>(part_ml + (base + lane) * 2);
+    ms = ml.x;
+    ls = ml.y;
   }
-  out[(int64_t)blockIdx.x * D + threadIdx.x] = f2h(O / L);
+  const float M = wave_max(ms);                               // whole waves only: blockDim >= 64
+  const float sc = __builtin_amdgcn_exp2f(ms - M);           // lanes >= ns: 2^-inf = 0
+  const float L = wave_sum(ls * sc);
+  const int dd = min((int)threadIdx.x, D - 1);
+  const float* po = part_o + base * D + dd;
+  float O = 0.f;
+  for (int s0 = 0; s0 < ns; s0 += 4) {
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = s0 + u < ns ? po[(int64_t)(s0 + u) * D] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) O += v[u] * __shfl(sc, (s0 + u) & 31);
+  }
+  if (threadIdx.x < D) out[(int64_t)blockIdx.x * D + dd] = f2h(O / L);
 }
 
 // ----------------------------------------------------------------- prefill
@@ -482,7 +496,7 @@ hipError_t launch_attn_decode(hipStream_t s, const f16* q, int M, RowMeta rm, Se
   attn_decode_kernel<DD><<<grid, 256, 0, s>>>(q, rm, st, arena_layer, geom, n_q_heads, chunk,      \
                                                n_splits, scale_log2, part_o, part_ml, out);        \
   if (n_splits > 1)                                                                                \
-    attn_merge_kernel<DD><<<M * n_q_heads, DD, 0, s>>>(part_o, part_ml, rm, n_q_heads, chunk,      \
+    attn_merge_kernel<DD><<<M * n_q_heads, DD < 64 ? 64 : DD, 0, s>>>(part_o, part_ml, rm, n_q_heads, chunk,      \
                                                        n_splits, out);
   switch (geom.head_dim) {
     case 32: AREAL_DEC(32) break;
