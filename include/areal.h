@@ -177,6 +177,27 @@ int areal_update_weights_interrupt(areal_ctx* ctx, const areal_weights* new_w,
                                    int32_t* live_seq_ids_out, float* logits_out,
                                    int64_t* reprefilled_tokens_out);
 
+/* Section 5.2, Eq. 5 (decoupled PPO objective): the proximal policy's token
+ * log-probabilities are recomputed over complete trajectories, with whatever
+ * parameters are loaded now, when a training batch has arrived.  For each
+ * packed sequence x_0 .. x_{L-1}:
+ *   logp_out[cu[i] + t] = log softmax(logits(x_0..x_{t-1}) / T)[x_t],  t >= 1,
+ *   logp_out[cu[i]]     = 0.
+ * One causal forward over all tokens (the prefill kernels, chunks of
+ * max_batch_tokens rows); the output projection and the log-sum-exp run over
+ * scratch_rows rows at a time, so logits for all tokens never exist at once.
+ * Live sequences are untouched: the pass borrows unused sequence slots and free
+ * KV blocks and returns them before it returns (AREAL_E_NOMEM, nothing
+ * queued, if there is no free slot or one sequence alone does not fit the free
+ * blocks).
+ *   tokens      host [cu_seqlens[n_seqs]]   packed sequences, each length >= 1
+ *   cu_seqlens  host [n_seqs+1]
+ *   logits_scratch  device float32 [scratch_rows, vocab], scratch_rows >= 1
+ *   logp_out    device float32 [cu_seqlens[n_seqs]] */
+int areal_recompute_logprob(areal_ctx* ctx, int32_t n_seqs, const int32_t* tokens,
+                            const int32_t* cu_seqlens, float temperature,
+                            float* logits_scratch, int32_t scratch_rows, float* logp_out);
+
 /* Termination (Section 4.1 "until the next interruption or termination"): the
  * caller decides when a sequence ends; its KV blocks return to the pool. */
 int areal_free_seq(areal_ctx* ctx, int32_t seq_id);

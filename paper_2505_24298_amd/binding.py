@@ -66,6 +66,8 @@ _SIGNATURES = {
                                        C.c_void_p]),
     "areal_update_weights_interrupt": (C.c_int, [C.c_void_p, C.POINTER(Weights), C.c_uint64, _I32P,
                                                  _I32P, C.c_void_p, _I64P]),
+    "areal_recompute_logprob": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_float, C.c_void_p,
+                                          C.c_int32, C.c_void_p]),
     "areal_free_seq": (C.c_int, [C.c_void_p, C.c_int32]),
     "areal_seq_len": (C.c_int, [C.c_void_p, C.c_int32, _I32P]),
     "areal_get_tokens": (C.c_int, [C.c_void_p, C.c_int32, _I32P]),
@@ -219,6 +221,23 @@ class Areal:
         self._weights_keepalive = self._weights_keepalive[-1:] + [keep]
         n = n_live.value
         return ids[:n].copy(), logits_out[:n], retok.value
+
+    def recompute_logprob(self, seqs, temperature=1.0, scratch_rows=256, scratch=None):
+        """Log-prob of every token of every sequence given the tokens before it
+        (packed float32 device tensor; first token of each sequence = 0)."""
+        torch = self.torch
+        cu = np.zeros(len(seqs) + 1, dtype=np.int32)
+        cu[1:] = np.cumsum([len(p) for p in seqs])
+        toks, toks_p = _i32(np.concatenate([np.asarray(p, dtype=np.int32) for p in seqs])
+                            if len(seqs) else np.zeros(0, dtype=np.int32))
+        if scratch is None:
+            scratch = torch.empty((scratch_rows, self.vocab), dtype=torch.float32, device=self.device)
+        assert scratch.is_cuda and scratch.dtype == torch.float32 and scratch.is_contiguous()
+        out = torch.empty(int(cu[-1]), dtype=torch.float32, device=self.device)
+        self._check(self.L.areal_recompute_logprob(self.ctx, len(seqs), toks_p, cu.ctypes.data_as(_I32P),
+                                                   float(temperature), scratch.data_ptr(),
+                                                   int(scratch.shape[0]), out.data_ptr()))
+        return out
 
     # -- generate ------------------------------------------------------------
     def prefill(self, seq_ids, prompts, logits_out=None):

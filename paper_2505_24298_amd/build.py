@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libareal.so")
-SOURCES = ["elementwise.hip", "gemm.hip", "attention.hip", "sampler.hip", "runtime.hip"]
+SOURCES = ["elementwise.hip", "gemm.hip", "attention.hip", "sampler.hip", "scoring.hip", "runtime.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed float32 VALU forms are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

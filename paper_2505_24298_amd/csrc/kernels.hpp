@@ -74,4 +74,11 @@ hipError_t launch_sampler(hipStream_t s, int n, int vocab, const float* logits, 
                           const int32_t* positions, float inv_temperature, float top_p, uint64_t seed,
                           const int32_t* forced, int32_t* tokens_out, float* logp_behav, float* logp_full);
 
+// ---- scoring.hip ------------------------------------------------------------
+// Row r with target[r] >= 0: out[r + 1] = log softmax(logits[r] * inv_t)[target[r]];
+// rows with pos[r] == 0 also set out[r] = 0.  (Rows are consecutive tokens of
+// packed sequences: row r predicts the token stored at r + 1.)
+hipError_t launch_token_logprob(hipStream_t s, const float* logits, int n, int vocab, float inv_t,
+                                const int32_t* target, const int32_t* pos, float* out);
+
 }  // namespace areal

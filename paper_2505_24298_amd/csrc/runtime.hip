@@ -285,6 +285,12 @@ struct PassArgs {
   int n_out;                      // logits rows produced
   float* logits;                  // device [n_out, vocab]
   double attn_units;              // context tokens read (decode) / query-key pairs (prefill)
+  // scoring passes (teacher-forced log-probs of every row's next token)
+  const int32_t* target = nullptr;   // device [M]: token each row predicts, -1 = none
+  float inv_t = 1.f;
+  float* scratch = nullptr;          // device float32 [scratch_rows, vocab]
+  int scratch_rows = 0;
+  float* logp = nullptr;             // device: entry of row 0 in the packed output
 };
 
 int run_pass(areal_ctx* c, const PassArgs& a) {
@@ -354,6 +360,22 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
       HIP_TRY(c, launch_gemm_cfg(s, act, wd, h, a.M, H, F, H, GEMM_ADD_F32, -1, -1));
     }
   }
+  if (a.target) {
+    // every row feeds the output projection, scratch_rows rows at a time: the
+    // [M, vocab] logits never exist as a whole
+    HIP_TRY(c, launch_rmsnorm(s, h, w.final_norm, xn, a.M, H, g.rms_eps, nullptr));
+    GemmW wl{{w.lm_head, nullptr, nullptr}, {g.vocab, 0, 0}};
+    for (int r0 = 0; r0 < a.M; r0 += a.scratch_rows) {
+      const int rows_now = std::min(a.scratch_rows, a.M - r0);
+      {
+        ProfScope ps(c, AREAL_K_GEMM_LMHEAD, -1, sampled, (double)rows_now);
+        HIP_TRY(c, launch_gemm(s, xn + (int64_t)r0 * H, wl, a.scratch, rows_now, g.vocab, H, g.vocab,
+                               GEMM_STORE_F32));
+      }
+      HIP_TRY(c, launch_token_logprob(s, a.scratch, rows_now, g.vocab, a.inv_t, a.target + r0, a.rm.pos + r0,
+                                      a.logp + r0));
+    }
+  }
   if (a.n_out > 0) {
     HIP_TRY(c, launch_rmsnorm(s, h, w.final_norm, xlast, a.n_out, H, g.rms_eps, a.last_rows));
     ProfScope ps(c, AREAL_K_GEMM_LMHEAD, -1, sampled, (double)a.n_out);
@@ -365,8 +387,16 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
 
 // Prefill-style passes over `spans` (prompt tokens given, or history re-read when
 // tokens == null).  install_blocks: rows at block starts install their block id.
+struct ScoreArgs {                // scoring: spans are consecutive sequences of one packed token array
+  float inv_t;
+  float* scratch;
+  int scratch_rows;
+  float* logp_out;                // device [total tokens], packed like `tokens`
+};
+
 int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* tokens,
-              const std::vector<int64_t>& tok_offset, bool install_blocks, float* logits_out) {
+              const std::vector<int64_t>& tok_offset, bool install_blocks, float* logits_out,
+              const ScoreArgs* score = nullptr) {
   const areal_model_cfg& g = c->cfg;
   auto passes = plan_passes(spans, g.max_batch_tokens);
   const int tile_rows = attn_prefill_tile_rows(g.n_q_heads, g.n_kv_heads);
@@ -380,7 +410,8 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
       n_work += (p.len + tile_rows - 1) / tile_rows;
       if (p.out_index >= 0) ++n_out;
     }
-    const uint64_t bytes = align_up((uint64_t)M * 4, 64) * 4 + align_up((uint64_t)n_work * sizeof(AttnWork), 64) +
+    if (score) n_out = 0;                                 // no last-row logits
+    const uint64_t bytes = align_up((uint64_t)M * 4, 64) * 5 + align_up((uint64_t)n_work * sizeof(AttnWork), 64) +
                            align_up((uint64_t)std::max(n_out, 1) * 4, 64);
     int rc = ring_begin(c, bytes);
     if (rc) return rc;
@@ -389,6 +420,9 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
     Staged s_tok = ring_take(c, (uint64_t)M * 4), s_nb = ring_take(c, (uint64_t)M * 4);
     Staged s_work = ring_take(c, (uint64_t)n_work * sizeof(AttnWork));
     Staged s_last = ring_take(c, (uint64_t)std::max(n_out, 1) * 4);
+    Staged s_tgt = ring_take(c, (uint64_t)M * 4);
+    int32_t* htgt = (int32_t*)s_tgt.host;
+    int64_t pass_base = -1;                               // packed index of the pass's row 0
     int32_t *hslot = (int32_t*)s_slot.host, *hpos = (int32_t*)s_pos.host, *htok = (int32_t*)s_tok.host,
             *hnb = (int32_t*)s_nb.host, *hlast = (int32_t*)s_last.host;
     AttnWork* hwork = (AttnWork*)s_work.host;
@@ -402,6 +436,11 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
         hslot[p.row0 + r] = p.slot;
         hpos[p.row0 + r] = pos;
         if (tokens) htok[p.row0 + r] = tokens[tok_offset[span_i] + done_in_span + r];
+        if (score) {
+          const int64_t gi = tok_offset[span_i] + done_in_span + r;
+          if (pass_base < 0) pass_base = gi - (p.row0 + r);
+          htgt[p.row0 + r] = pos + 1 < spans[span_i].len ? tokens[gi + 1] : -1;
+        }
         hnb[p.row0 + r] = (install_blocks && pos % AREAL_KV_BLOCK_TOKENS == 0) ? blocks[pos / AREAL_KV_BLOCK_TOKENS] : -1;
       }
       for (int r = 0; r < p.len; r += tile_rows)
@@ -409,7 +448,7 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
       done_in_span += p.len;
       if (p.out_index >= 0) {
         if (first_out < 0) first_out = p.out_index;
-        hlast[oi++] = p.row0 + p.len - 1;
+        if (!score) hlast[oi++] = p.row0 + p.len - 1;
         ++span_i;
         done_in_span = 0;
       }
@@ -428,6 +467,13 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
     a.n_out = n_out;
     a.logits = n_out > 0 ? logits_out + (int64_t)first_out * g.vocab : nullptr;
     a.attn_units = qk_pairs;
+    if (score) {
+      a.target = (const int32_t*)s_tgt.dev;
+      a.inv_t = score->inv_t;
+      a.scratch = score->scratch;
+      a.scratch_rows = score->scratch_rows;
+      a.logp = score->logp_out + pass_base;
+    }
     rc = run_pass(c, a);
     if (rc) return rc;
   }
@@ -705,6 +751,54 @@ int areal_update_weights_interrupt(areal_ctx* c, const areal_weights* new_w, uin
   // old K/V is never read again: every position is rewritten under the new
   // weights, in position order, before any later position attends to it
   return run_spans(c, spans, nullptr, {}, false, logits_out);
+}
+
+int areal_recompute_logprob(areal_ctx* c, int32_t n, const int32_t* tokens, const int32_t* cu,
+                            float temperature, float* scratch, int32_t scratch_rows, float* logp_out) {
+  if (!c) return AREAL_E_INVAL;
+  if (!c->have_weights) return fail(c, AREAL_E_STATE, "no weights loaded");
+  if (n == 0) return AREAL_OK;
+  if (n < 0 || !tokens || !cu || !scratch || !logp_out || scratch_rows < 1)
+    return fail(c, AREAL_E_INVAL, "NULL argument, negative count or no scratch rows");
+  if (!(temperature > 0.f)) return fail(c, AREAL_E_INVAL, "temperature must be > 0");
+  const areal_model_cfg& g = c->cfg;
+  if (cu[0] != 0) return fail(c, AREAL_E_INVAL, "cu_seqlens[0] must be 0");
+  std::vector<int> free_slots;
+  for (int id = 0; id < g.max_seqs; ++id)
+    if (!c->seqs[id].live) free_slots.push_back(id);
+  if (free_slots.empty()) return fail(c, AREAL_E_NOMEM, "no free sequence slot to score with");
+  for (int i = 0; i < n; ++i) {
+    const int64_t len = (int64_t)cu[i + 1] - cu[i];
+    if (len < 1) return fail(c, AREAL_E_INVAL, "every sequence needs at least one token");
+    if (len > g.max_seq_len) return fail(c, AREAL_E_NOMEM, "sequence longer than max_seq_len");
+    if (c->alloc->blocks_for(len) > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena too small to score this sequence");
+  }
+  for (int64_t t = 0; t < cu[n]; ++t)
+    if (tokens[t] < 0 || tokens[t] >= g.vocab) return fail(c, AREAL_E_INVAL, "token id outside the vocabulary");
+  ScoreArgs sa{1.0f / temperature, scratch, scratch_rows, logp_out};
+  // groups of consecutive sequences that fit the free slots and blocks; their
+  // K/V lives in borrowed blocks that go back to the pool once the passes are
+  // queued (later passes that reuse them are ordered after on the stream)
+  int i = 0;
+  while (i < n) {
+    std::vector<Span> spans;
+    std::vector<int64_t> tok_off;
+    int64_t blocks = 0;
+    while (i < n && spans.size() < free_slots.size()) {
+      const int len = cu[i + 1] - cu[i];
+      const int64_t nb = c->alloc->blocks_for(len);
+      if (blocks + nb > c->alloc->n_free()) break;
+      blocks += nb;
+      spans.push_back(Span{free_slots[spans.size()], 0, len, (int)spans.size()});
+      tok_off.push_back(cu[i]);
+      ++i;
+    }
+    for (auto& sp : spans) c->alloc->reserve(sp.slot, sp.len);
+    const int rc = run_spans(c, spans, tokens, tok_off, true, nullptr, &sa);
+    for (auto& sp : spans) c->alloc->release(sp.slot);
+    if (rc) return rc;
+  }
+  return AREAL_OK;
 }
 
 int areal_free_seq(areal_ctx* c, int32_t id) {

@@ -1,0 +1,64 @@
+// Log-probability of one given token per row of float32 logits:
+//   out = z[tok] - max z - log sum_i exp(z_i - max z),   z = logits * (1/T).
+// One work-group per row, one pass over the row: every thread keeps a running
+// (max, sum of exponentials) pair over its elements, the pairs are combined
+// across the wave with shuffles and across waves through LDS.
+#include "kernels.hpp"
+
+namespace areal {
+namespace {
+
+constexpr int LP_THREADS = 1024;
+
+__device__ __forceinline__ void lse_combine(float& m, float& s, float m2, float s2) {
+  const float mn = fmaxf(m, m2);
+  const float mu = mn == -INFINITY ? 0.f : mn;
+  s = s * __expf(m - mu) + s2 * __expf(m2 - mu);
+  m = mn;
+}
+
+__global__ __launch_bounds__(LP_THREADS) void token_logprob_kernel(
+    const float* __restrict__ logits, int vocab, float inv_t, const int32_t* __restrict__ target,
+    const int32_t* __restrict__ pos, float* __restrict__ out) {
+  __shared__ float sm[LP_THREADS / 64], ss[LP_THREADS / 64];
+  const int row = blockIdx.x;
+  const int tok = target[row];
+  if (pos[row] == 0 && threadIdx.x == 0) out[row] = 0.f;      // nothing predicts a first token
+  if (tok < 0) return;                                        // last token of its sequence
+  const float* z = logits + (int64_t)row * vocab;
+  float m = -INFINITY, s = 0.f;
+  const int n4 = (vocab & 3) ? 0 : vocab >> 2;             // rows are 16-byte aligned only then
+  for (int i = threadIdx.x; i < n4; i += LP_THREADS) {
+    const float4 v = reinterpret_cast<const float4*>(z)[i];
+    const float a = v.x * inv_t, b = v.y * inv_t, c = v.z * inv_t, d = v.w * inv_t;
+    const float mn = fmaxf(fmaxf(fmaxf(a, b), fmaxf(c, d)), m);
+    s = s * __expf(m - mn) + __expf(a - mn) + __expf(b - mn) + __expf(c - mn) + __expf(d - mn);
+    m = mn;
+  }
+  for (int i = (n4 << 2) + threadIdx.x; i < vocab; i += LP_THREADS) lse_combine(m, s, z[i] * inv_t, 1.f);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) lse_combine(m, s, __shfl_xor(m, o), __shfl_xor(s, o));
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) { sm[wave] = m; ss[wave] = s; }
+  __syncthreads();
+  if (wave == 0) {
+    m = lane < LP_THREADS / 64 ? sm[lane] : -INFINITY;
+    s = lane < LP_THREADS / 64 ? ss[lane] : 0.f;
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) lse_combine(m, s, __shfl_xor(m, o), __shfl_xor(s, o));
+    if (lane == 0) out[row + 1] = z[tok] * inv_t - m - __logf(s);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_token_logprob(hipStream_t s, const float* logits, int n, int vocab, float inv_t,
+                                const int32_t* target, const int32_t* pos, float* out) {
+  if (n <= 0 || vocab <= 0 || !logits || !target || !pos || !out || !(inv_t > 0.f) ||
+      ((uintptr_t)logits & 15))
+    return hipErrorInvalidValue;
+  token_logprob_kernel<<<n, LP_THREADS, 0, s>>>(logits, vocab, inv_t, target, pos, out);
+  return hipGetLastError();
+}
+
+}  // namespace areal

@@ -12,6 +12,9 @@
       > 1 GB so they come from HBM.
   python3 paper_2505_24298_amd/microbench.py prefill
       prefill of 32x256, 8x2048, 4x8000 tokens: per-kernel time of one layer.
+  python3 paper_2505_24298_amd/microbench.py score
+      teacher-forced log-prob pass over 64 trajectories of 512..4096 tokens at the
+      1.5B shape, output projection over 256 / 1024 / 4096 rows at a time.
 """
 from __future__ import annotations
 
@@ -146,6 +149,36 @@ def prefill():
         del eng
 
 
+def score():
+    import torch
+    from paper_2505_24298_amd import binding, synth
+    cfg = synth.shape("qwen2-1.5b")
+    w = _weights(torch, cfg)
+    rng = np.random.default_rng(4)
+    lens = rng.integers(512, 4097, size=64)
+    seqs = [rng.integers(0, cfg["vocab"], size=int(n)).astype(np.int32) for n in lens]
+    total = int(lens.sum())
+    eng = binding.Areal(cfg, max_seqs=64, max_seq_len=4096, max_batch_tokens=8192, kv_blocks=total // 16 + 128)
+    eng.load_weights(w, 0)
+    flops_tok = 2.0 * (1543656960 - 0)          # all matrices incl. the output projection, per token
+    attn = 4.0 * cfg["n_q_heads"] * cfg["head_dim"] * cfg["n_layers"] * float((lens * (lens + 1) / 2).sum())
+    for rows in (256, 1024, 4096):
+        scratch = torch.empty((rows, cfg["vocab"]), dtype=torch.float32, device="cuda")
+        eng.recompute_logprob(seqs[:2], 1.0, scratch=scratch)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        out = eng.recompute_logprob(seqs, 1.0, scratch=scratch)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        print(json.dumps(dict(sequences=64, tokens=total, scratch_rows=rows, ms=round(ms, 1),
+                              tokens_per_s=round(total / ms * 1e3),
+                              TFLOPs=round((flops_tok * total + attn) / (ms * 1e-3) / 1e12, 1),
+                              mean_logp=round(float(out.mean()), 3))), flush=True)
+        del scratch
+    eng.close()
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else ""
     if what == "attn-decode":
@@ -155,6 +188,8 @@ if __name__ == "__main__":
              sys.argv[3] if len(sys.argv) > 3 else "qkv,o,gateup,down,lmhead")
     elif what == "prefill":
         prefill()
+    elif what == "score":
+        score()
     else:
         print(__doc__)
         sys.exit(2)

@@ -57,11 +57,17 @@ def test_qwen2_1p5b_shape_slice_with_interrupt():
     for s in ids:
         assert eng.get_tokens(s).tolist() == prompts[s].tolist() + forced[s].tolist()
         assert eng.get_versions(s).tolist() == [-1] * plen[s] + [0] * t_int + [1] * (n_new - t_int)
+    # trajectories done: recompute their token log-probs under the weights loaded now (version 1)
+    for s in ids:
+        eng.free_seq(s)
+    full = [np.concatenate([prompts[s], forced[s]]) for s in ids]
+    rescored = eng.recompute_logprob(full, 1.0, scratch_rows=64).cpu().numpy()
+    cu = np.concatenate([[0], np.cumsum([len(x) for x in full])])
     eng.close()
     got_logits = np.stack(got_logits)            # [n_new, n_seq, V]
 
     # ---- oracle: dense pass per version over prompt + forced tokens ----
-    worst_logit = worst_lb = worst_lf = 0.0
+    worst_logit = worst_lb = worst_lf = worst_score = 0.0
     for ver, (wd, steps) in enumerate([(w0, range(0, t_int)), (w1, range(t_int, n_new))]):
         wo = _to_oracle(wd)
         for s in ids:
@@ -74,9 +80,13 @@ def test_qwen2_1p5b_shape_slice_with_interrupt():
                                                forced=int(forced[s, t]))
                 worst_lb = max(worst_lb, abs(float(got_lb[t][s]) - lb))
                 worst_lf = max(worst_lf, abs(float(got_lf[t][s]) - lf))
+                if ver == 1:      # the scoring pass ran under version 1 over the whole sequence
+                    worst_score = max(worst_score, abs(float(rescored[cu[s] + plen[s] + t]) - lf))
         del wo
-    print(f"1.5B shape: logits {worst_logit:.2e}  logp_behav {worst_lb:.2e}  logp_full {worst_lf:.2e}")
+    print(f"1.5B shape: logits {worst_logit:.2e}  logp_behav {worst_lb:.2e}  logp_full {worst_lf:.2e}  "
+          f"recomputed logp {worst_score:.2e}")
     assert worst_logit <= LOGIT_TOL and worst_lb <= LOGP_TOL and worst_lf <= LOGP_TOL
+    assert worst_score <= LOGP_TOL
 
 
 def test_qwen2_7b_dimensions_four_layers_top_p():
