@@ -4,7 +4,7 @@
 // KV head, for one sequence; prefill: 16 consecutive query positions of one
 // head) and walks KV blocks of 16 tokens with an online softmax:
 //   S^T[token, row] = K_tile . Q^T      v_mfma_f32_16x16x32_f16, K straight
-//                                       from HBM in its row-major tile layout
+//                                       from HBM (tiles stored in operand order)
 //   P = exp2(S^T - m)                   float32, per-row running max / sum
 //   O[row, :] += P . V_tile             v_mfma_f32_16x16x16_f16; the 
 //                                       accumulator layout of S^T is already
@@ -30,35 +30,6 @@ __device__ __forceinline__ f32x4 mfma_qk(f16x8 a, f16x8 b, f32x4 c) {
 }
 __device__ __forceinline__ f32x4 mfma_pv(f16x4 p, f16x4 v, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x16f16(p, v, c, 0, 0, 0);
-}
-
-// Issue the loads of NB blocks starting at logical block `b` (blocks >= b_end
-// are skipped and read as zero).
-template <int D>
-__device__ __forceinline__ void load_group(KvFrag<D>& f, const f16* __restrict__ arena,
-                                           const KvGeom& geom, const int32_t* __restrict__ table,
-                                           int b, int b_end, int kvh, int lane) {
-  const int g = lane >> 4, j = lane & 15;
-  const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-  for (int u = 0; u < NB; ++u) {
-    if (b + u < b_end) {
-      const int blk = table[b + u];
-      const f16* kt = arena + kv_tile_off(geom, blk, kvh, 0) + j * D + g * (D / 4);
-      const f16* vt = arena + kv_tile_off(geom, blk, kvh, 1) + lane * (D / 4);
-#pragma unroll
-      for (int c = 0; c < D / 32; ++c) {
-        f.k[u][c] = ld8(kt + c * 8);
-        f.v[u][c] = ld8(vt + c * 8);
-      }
-    } else {
-#pragma unroll
-      for (int c = 0; c < D / 32; ++c) {
-        f.k[u][c] = zero8;
-        f.v[u][c] = zero8;
-      }
-    }
-  }
 }
 
 // One online-softmax update over the NB blocks held in `f`.
@@ -140,12 +111,13 @@ __device__ __forceinline__ void load_group_ids(KvFrag<D>& f, const f16* __restri
   for (int u = 0; u < NB; ++u) {
     if (b + u < b_end) {                               // wave-uniform
       const int blk = block_id(ids, b + u - b0);
-      const f16* kt = arena + kv_tile_off(geom, blk, kvh, 0) + j * D + g * (D / 4);
-      const f16* vt = arena + kv_tile_off(geom, blk, kvh, 1) + lane * (D / 4);
+      // both tiles are stored chunk-major in operand order: load c of a wave reads 1 KiB in a row
+      const f16* kt = arena + kv_tile_off(geom, blk, kvh, 0) + lane * 8;
+      const f16* vt = arena + kv_tile_off(geom, blk, kvh, 1) + lane * 8;
 #pragma unroll
       for (int c = 0; c < D / 32; ++c) {
-        f.k[u][c] = ld8(kt + c * 8);
-        f.v[u][c] = ld8(vt + c * 8);
+        f.k[u][c] = ld8(kt + c * 512);
+        f.v[u][c] = ld8(vt + c * 512);
       }
     } else {
 #pragma unroll
@@ -183,9 +155,9 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   f16x8 qf[D / 32];
   {
     const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const f16* qp = q + ((int64_t)i * nq + kvh * G + j) * D + g * (D / 4);
+    const f16* qp = q + ((int64_t)i * nq + kvh * G + j) * D + g * 8;   // same dim order as the K fragments
 #pragma unroll
-    for (int c = 0; c < D / 32; ++c) qf[c] = j < G ? ld8(qp + c * 8) : zero8;
+    for (int c = 0; c < D / 32; ++c) qf[c] = j < G ? ld8(qp + c * 32) : zero8;
   }
   float m = -INFINITY, l = 0.f;
   f32x4 o[D / 16];
@@ -399,10 +371,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
     const int slot = t * 64 + lane;
     if (!isv_ld) {                                   // K: slot (row, chunk ^ row) <- chunk of that row
       const int row = slot / CPR, c = (slot % CPR) ^ (row & (CPR - 1));
-      src_off[t] = row * D + c * 8;
+      src_off[t] = k_tile_index(row, c * 8);
     } else {                                         // V: slot (lane, i ^ f(lane)) <- chunk i of that lane
       const int ln = slot / NCH, i = (slot % NCH) ^ ((ln >> 2) & (NCH - 1));
-      src_off[t] = (ln * NCH + i) * 8;
+      src_off[t] = (i * 64 + ln) * 8;
     }
   }
   int id_chunk = -1, ids = 0;

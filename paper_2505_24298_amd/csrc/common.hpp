@@ -59,10 +59,14 @@ __device__ __forceinline__ void wait_vmcnt(int n) {
 
 // ---- paged KV arena addressing --------------------------------------------
 // arena = [layer][block][kv_head][K tile | V tile], tiles of 16*d halves.
-//   K tile: [token 0..15][d]                       (row-major)
-//   V tile: [lane 0..63][n 0..d/16-1][t 0..3] with lane = g*16 + j holding
-//           V[token 4g+t][dim 16n+j]: exactly the B operand of the 16x16x16
-//           MFMA that multiplies probabilities by values, 64 B per lane.
+//   K tile: [c 0..d/32-1][g 0..3][token 0..15][e 0..7] holding K[token][dim 32c+8g+e]:
+//           the 16 bytes at (c, lane = g*16 + token) are lane's A-operand
+//           registers of MFMA c of the 16x16x32 score product.
+//   V tile: [c 0..d/32-1][lane 0..63][e 0..7] with lane = g*16 + j and
+//           e = 4*(n&1) + t holding V[token 4g+t][dim 16n+j], n = 2c + (e>>2):
+//           the 16 bytes at (c, lane) are lane's B-operand registers of the
+//           16x16x16 MFMAs n = 2c, 2c+1 that multiply probabilities by values,
+//           and one load instruction of a wave (fixed c) reads 1 KiB in a row.
 struct KvGeom {
   int n_kv_heads, head_dim;
   int64_t layer_stride;   // elements between layers = n_blocks * block_stride
@@ -71,9 +75,13 @@ struct KvGeom {
 __device__ __forceinline__ int64_t kv_tile_off(const KvGeom& g, int block, int kvh, int is_v) {
   return (int64_t)block * g.block_stride + (int64_t)(kvh * 2 + is_v) * (kBlockTokens * g.head_dim);
 }
+__device__ __forceinline__ int k_tile_index(int token, int dim) {
+  return (((dim >> 5) * 64 + ((dim >> 3) & 3) * 16 + token) * 8) + (dim & 7);
+}
 __device__ __forceinline__ int v_tile_index(int head_dim, int token, int dim) {
+  (void)head_dim;
   int g = token >> 2, t = token & 3, n = dim >> 4, j = dim & 15;
-  return (((g * 16 + j) * (head_dim >> 4)) + n) * 4 + t;
+  return (((n >> 1) * 64 + g * 16 + j) * 8) + (n & 1) * 4 + t;
 }
 
 }  // namespace areal

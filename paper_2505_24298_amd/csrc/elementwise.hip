@@ -132,9 +132,9 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(
       qo[j] = f2h(y1);
       qo[j + half] = f2h(y2);
     } else {
-      f16* kt = arena_layer + kv_tile_off(geom, blk, head - nq, 0) + tin * d;
-      kt[j] = f2h(y1);
-      kt[j + half] = f2h(y2);
+      f16* kt = arena_layer + kv_tile_off(geom, blk, head - nq, 0);
+      kt[k_tile_index(tin, j)] = f2h(y1);
+      kt[k_tile_index(tin, j + half)] = f2h(y2);
     }
   }
   const float* vrow = row + (nq + nkv) * d;

@@ -124,6 +124,8 @@ struct areal_ctx {
   hipEvent_t seg_done[kRingSegs];
   bool seg_recorded[kRingSegs];
   std::string err;
+  int split_target = 3072;              // decode attention: work-groups per launch aimed at
+  int min_chunk = 256;
   // measurement hook
   int prof_class = -1, prof_layer = 0, prof_every = 1;
   int64_t prof_pass = 0;
@@ -510,6 +512,14 @@ int areal_create(const areal_model_cfg* cfg, areal_ctx** out) {
     return fail(nullptr, AREAL_E_NOMEM, "kv_arena missing, misaligned or smaller than one block");
   areal_ctx* c = new areal_ctx();
   c->cfg = *cfg;
+  if (const char* e = getenv("AREAL_DECODE_SPLIT_TARGET")) {   // tuning knob for sweeps
+    const int v = atoi(e);
+    if (v >= 64 && v <= 65536) c->split_target = v;
+  }
+  if (const char* e = getenv("AREAL_DECODE_MIN_CHUNK")) {
+    const int v = atoi(e);
+    if (v == 128 || v == 256 || v == 384 || v == 512) c->min_chunk = v;
+  }
   c->lay = lay;
   c->stream = reinterpret_cast<hipStream_t>(cfg->hip_stream);
   c->ws = reinterpret_cast<char*>(cfg->workspace);
@@ -666,9 +676,11 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
   rc = ring_flush(c, start);
   if (rc) return rc;
   // split the KV walk so that the grid holds a few work-groups per compute unit
-  // (targets of 512 .. 4096 work-groups measured within 5 % of each other on the rollout's context mixes)
-  int64_t chunk = (sum_ctx * g.n_kv_heads / 2048 + 127) / 128 * 128;
-  chunk = std::min<int64_t>(std::max<int64_t>(chunk, 256), 2048);   // a split spans at most 128 blocks
+  // (targets of 768 .. 6144 work-groups and minimum splits of 128 .. 512 tokens measured within
+  // 5 % of each other on the rollout's context mixes; environment knobs AREAL_DECODE_SPLIT_TARGET
+  // and AREAL_DECODE_MIN_CHUNK, read at areal_create, repeat that sweep)
+  int64_t chunk = (sum_ctx * g.n_kv_heads / c->split_target + 127) / 128 * 128;
+  chunk = std::min<int64_t>(std::max<int64_t>(chunk, c->min_chunk), 2048);   // a split spans at most 128 blocks
   int n_splits = (int)((max_ctx + chunk - 1) / chunk);
   if (n_splits > kMaxSplits) {
     chunk = ((max_ctx + kMaxSplits - 1) / kMaxSplits + 127) / 128 * 128;
