@@ -66,7 +66,8 @@ typedef struct {
                                   library converts them to half precision (nearest even)
                                   into space reserved in the workspace.  0: only half-
                                   precision sets, read in place                           */
-  void*    kv_arena;           /* device; paged K/V pool, any size >= one block           */
+  void*    kv_arena;           /* device; paged K/V pool, any size >= one block; cleared
+                                  by areal_create on hip_stream                           */
   uint64_t kv_arena_bytes;
   void*    workspace;          /* device; >= areal_workspace_bytes(cfg), 256-B aligned    */
   uint64_t workspace_bytes;

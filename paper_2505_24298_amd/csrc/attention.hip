@@ -129,49 +129,168 @@ __device__ __forceinline__ void load_group_ids(KvFrag<D>& f, const f16* __restri
   }
 }
 
+// Bias, rotate-half RoPE and rounding to half of one head vector of the float32
+// QKV row, delivered as this lane's MFMA fragments: lane group g gets dims
+// [32c + 8g, +8) for c = 0 .. D/32-1.  For D >= 64 a lane holds both members of
+// every rotation pair (dims x and x + D/2 sit in chunks c and c + D/64); for
+// D = 32 the partner sits in lane ^ 32.  Loading and rotating are separate steps
+// so that the caller can put other loads in flight between them.
+template <int D>
+struct RawHead {
+  float x[D / 32][8];
+};
+template <int D>
+struct RopeAngles {                       // cos / sin of this lane's rotation pairs
+  float c[D >= 64 ? D / 64 : 1][8], s[D >= 64 ? D / 64 : 1][8];
+};
+
+template <int D>
+__device__ __forceinline__ void load_raw(RawHead<D>& r, const float* __restrict__ src, int g) {
+#pragma unroll
+  for (int c = 0; c < D / 32; ++c) {
+    const float4 a = *reinterpret_cast<const float4*>(src + 32 * c + 8 * g);
+    const float4 b = *reinterpret_cast<const float4*>(src + 32 * c + 8 * g + 4);
+    r.x[c][0] = a.x; r.x[c][1] = a.y; r.x[c][2] = a.z; r.x[c][3] = a.w;
+    r.x[c][4] = b.x; r.x[c][5] = b.y; r.x[c][6] = b.z; r.x[c][7] = b.w;
+  }
+}
+template <int D>
+__device__ __forceinline__ void load_angles(RopeAngles<D>& a, const float* __restrict__ ct,
+                                            const float* __restrict__ sn, int g) {
+  constexpr int HC = D >= 64 ? D / 64 : 1;
+#pragma unroll
+  for (int c = 0; c < HC; ++c) {
+    const int j0 = D >= 64 ? 32 * c + 8 * g : (8 * g) & 15;
+    const float4 c0 = *reinterpret_cast<const float4*>(ct + j0), c1 = *reinterpret_cast<const float4*>(ct + j0 + 4);
+    const float4 s0 = *reinterpret_cast<const float4*>(sn + j0), s1 = *reinterpret_cast<const float4*>(sn + j0 + 4);
+    a.c[c][0] = c0.x; a.c[c][1] = c0.y; a.c[c][2] = c0.z; a.c[c][3] = c0.w;
+    a.c[c][4] = c1.x; a.c[c][5] = c1.y; a.c[c][6] = c1.z; a.c[c][7] = c1.w;
+    a.s[c][0] = s0.x; a.s[c][1] = s0.y; a.s[c][2] = s0.z; a.s[c][3] = s0.w;
+    a.s[c][4] = s1.x; a.s[c][5] = s1.y; a.s[c][6] = s1.z; a.s[c][7] = s1.w;
+  }
+}
+template <int D>
+__device__ __forceinline__ void rotate(RawHead<D>& r, const f16* __restrict__ bias, const RopeAngles<D>& a,
+                                       int g, f16x8 (&out)[D / 32]) {
+  if (bias) {
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c) {
+      const f16x8 bb = ld8(bias + 32 * c + 8 * g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) r.x[c][e] += h2f(bb[e]);
+    }
+  }
+  if constexpr (D >= 64) {
+    constexpr int HC = D / 64;
+#pragma unroll
+    for (int c = 0; c < HC; ++c)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x1 = r.x[c][e], x2 = r.x[c + HC][e];
+        out[c][e] = f2h(x1 * a.c[c][e] - x2 * a.s[c][e]);
+        out[c + HC][e] = f2h(x2 * a.c[c][e] + x1 * a.s[c][e]);
+      }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float xp = __shfl_xor(r.x[0][e], 32);
+      out[0][e] = f2h(g < 2 ? r.x[0][e] * a.c[0][e] - xp * a.s[0][e] : r.x[0][e] * a.c[0][e] + xp * a.s[0][e]);
+    }
+  }
+}
+
 // One work-group per (split, kv head, sequence); the partials of a sequence cut
-// into several splits are combined by attn_merge_kernel.
+// into several splits are combined by attn_merge_kernel.  The row's query heads
+// are taken from the float32 QKV row (bias, RoPE, rounding done here).  The
+// cached positions 0 .. pos-1 come from the paged arena; the token being
+// appended (position pos) is handled by the work-group whose split contains
+// pos: it rotates and rounds the new key, stores key and value into the
+// sequence's block for later steps, and folds the new token into its softmax
+// state as one more (score, value) pair.
 template <int D>
 __global__ __launch_bounds__(256) void attn_decode_kernel(
-    const f16* __restrict__ q, RowMeta rm, SeqState st, const f16* __restrict__ arena, KvGeom geom,
-    int nq, int chunk, int n_splits, float scale_log2, float* __restrict__ part_o,
-    float* __restrict__ part_ml, f16* __restrict__ out) {
+    const float* __restrict__ qkv, RowMeta rm, SeqState st, const f16* __restrict__ bq,
+    const f16* __restrict__ bk, const f16* __restrict__ bv, const float* __restrict__ cos_tab,
+    const float* __restrict__ sin_tab, f16* __restrict__ arena, KvGeom geom, int nq, int chunk,
+    int n_splits, float scale_log2, float* __restrict__ part_o, float* __restrict__ part_ml,
+    f16* __restrict__ out) {
   __shared__ float sm[4][16], sl[4][16];
   __shared__ float so[4][16][D];
+  __shared__ float s_new[16], v_new[D];
   const int i = blockIdx.z, kvh = blockIdx.y, split = blockIdx.x;
-  const int pos = rm.pos[i], ctx = pos + 1;
+  const int pos = rm.pos[i];
   const int t0 = split * chunk;
-  if (t0 >= ctx) return;
-  const int t1 = min(ctx, t0 + chunk);
+  if (t0 > pos) return;
+  const bool owner = pos < t0 + chunk;                 // this split holds the appended position
+  const int t1 = min(pos, t0 + chunk);                 // cached tokens [t0, t1)
   const int b0 = t0 / kBlockTokens, b1 = (t1 + kBlockTokens - 1) / kBlockTokens;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, j = lane & 15;
-  const int G = nq / geom.n_kv_heads;
+  const int nkv = geom.n_kv_heads, G = nq / nkv;
   const int32_t* table = st.table + (int64_t)rm.slot[i] * st.max_blocks;
   BlockIds ids;
   ids.lo = b0 + lane < b1 ? table[b0 + lane] : 0;
   ids.hi = b0 + 64 + lane < b1 ? table[b0 + 64 + lane] : 0;
 
+  // Loads go out in dependency order (the query row needs nothing, the angles need pos,
+  // the K/V tiles need the block ids) and the rotation runs while the tiles are in flight.
+  const float* row = qkv + (int64_t)i * (nq + 2 * nkv) * D;
+  const int head = kvh * G + min(j, G - 1);
+  RawHead<D> qraw;
+  load_raw<D>(qraw, row + head * D, g);
+  RopeAngles<D> ang;
+  load_angles<D>(ang, cos_tab + (int64_t)pos * (D / 2), sin_tab + (int64_t)pos * (D / 2), g);
+
+  // wave w takes block groups w, w+4, ... of this split
+  int b = b0 + wave * NB;
+  KvFrag<D> cur, nxt;
+  if (b < b1) load_group_ids<D>(cur, arena, geom, ids, b0, b, b1, kvh, lane);
+
   f16x8 qf[D / 32];
-  {
+  rotate<D>(qraw, bq ? bq + head * D : nullptr, ang, g, qf);
+  if (j >= G) {
     const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const f16* qp = q + ((int64_t)i * nq + kvh * G + j) * D + g * 8;   // same dim order as the K fragments
 #pragma unroll
-    for (int c = 0; c < D / 32; ++c) qf[c] = j < G ? ld8(qp + c * 32) : zero8;
+    for (int c = 0; c < D / 32; ++c) qf[c] = zero8;
+  }
+  if (owner && wave == 0) {                            // wave-uniform
+    RawHead<D> kraw;
+    load_raw<D>(kraw, row + (nq + kvh) * D, g);
+    f16x8 kf[D / 32];
+    rotate<D>(kraw, bk ? bk + kvh * D : nullptr, ang, g, kf);
+    float dot = 0.f;
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dot += h2f(qf[c][e]) * h2f(kf[c][e]);
+    dot += __shfl_xor(dot, 16);
+    dot += __shfl_xor(dot, 32);
+    if (g == 0) s_new[j] = dot * scale_log2;
+    const int blk = table[pos / kBlockTokens], tin = pos % kBlockTokens;
+    if (j == 0) {
+      f16* kt = arena + kv_tile_off(geom, blk, kvh, 0);
+#pragma unroll
+      for (int c = 0; c < D / 32; ++c) *reinterpret_cast<f16x8*>(kt + k_tile_index(tin, 32 * c + 8 * g)) = kf[c];
+    }
+    f16* vt = arena + kv_tile_off(geom, blk, kvh, 1);
+    const float* vrow = row + (nq + nkv + kvh) * D;
+    for (int dim = lane; dim < D; dim += 64) {
+      float v = vrow[dim];
+      if (bv) v += h2f(bv[kvh * D + dim]);
+      const f16 hv = f2h(v);
+      v_new[dim] = h2f(hv);
+      vt[v_tile_index(D, tin, dim)] = hv;
+    }
   }
   float m = -INFINITY, l = 0.f;
   f32x4 o[D / 16];
 #pragma unroll
   for (int n = 0; n < D / 16; ++n) o[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // wave w takes block groups w, w+4, ... of this split
-  int b = b0 + wave * NB;
-  KvFrag<D> cur, nxt;
-  if (b < b1) load_group_ids<D>(cur, arena, geom, ids, b0, b, b1, kvh, lane);
   while (b < b1) {
     const int bn = b + 4 * NB;
     if (bn < b1) load_group_ids<D>(nxt, arena, geom, ids, b0, bn, b1, kvh, lane);
-    attend_group<D>(cur, qf, b, pos, scale_log2, m, l, o, lane);
+    attend_group<D>(cur, qf, b, pos - 1, scale_log2, m, l, o, lane);
     cur = nxt;
     b = bn;
   }
@@ -187,12 +306,21 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   for (int idx = threadIdx.x; idx < G * D; idx += 256) {
     const int h = idx / D, dd = idx - h * D;
     float M = fmaxf(fmaxf(sm[0][h], sm[1][h]), fmaxf(sm[2][h], sm[3][h]));
+    const float Mu = M == -INFINITY ? 0.f : M;               // no cached token in this split
     float L = 0.f, O = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float sc = __builtin_amdgcn_exp2f(sm[w][h] - M);   // idle wave: m = -inf -> 0
+      const float sc = __builtin_amdgcn_exp2f(sm[w][h] - Mu);  // idle wave: m = -inf -> 0
       L += sl[w][h] * sc;
       O += so[w][h][dd] * sc;
+    }
+    if (owner) {                                             // the appended token
+      const float sN = s_new[h];
+      const float M2 = fmaxf(M, sN);
+      const float a = __builtin_amdgcn_exp2f(M - M2), e = __builtin_amdgcn_exp2f(sN - M2);
+      L = L * a + e;
+      O = O * a + e * v_new[dd];
+      M = M2;
     }
     const int head = kvh * G + h;
     if (n_splits == 1) {
@@ -456,20 +584,24 @@ static bool geom_ok(const KvGeom& g, int nq) {
   return true;
 }
 
-hipError_t launch_attn_decode(hipStream_t s, const f16* q, int M, RowMeta rm, SeqState st,
-                              const f16* arena_layer, KvGeom geom, int n_q_heads, int chunk,
-                              int n_splits, float* part_o, float* part_ml, f16* out) {
+hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
+                              const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
+                              const float* sin_tab, f16* arena_layer, KvGeom geom, int n_q_heads,
+                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out) {
   if (M <= 0 || !geom_ok(geom, n_q_heads) || chunk <= 0 || chunk % (4 * NB * kBlockTokens) ||
-      chunk > 128 * kBlockTokens || n_splits <= 0 || (n_splits > 1 && (!part_o || !part_ml)))
+      chunk > 128 * kBlockTokens || n_splits <= 0 || (n_splits > 1 && (!part_o || !part_ml)) ||
+      !qkv || !cos_tab || !sin_tab || (bq && (!bk || !bv)) ||
+      (((uintptr_t)qkv | (uintptr_t)bq | (uintptr_t)bk | (uintptr_t)bv | (uintptr_t)arena_layer) & 15))
     return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)geom.head_dim);
   dim3 grid(n_splits, geom.n_kv_heads, M);
 #define AREAL_DEC(DD)                                                                              \
-  attn_decode_kernel<DD><<<grid, 256, 0, s>>>(q, rm, st, arena_layer, geom, n_q_heads, chunk,      \
-                                               n_splits, scale_log2, part_o, part_ml, out);        \
+  attn_decode_kernel<DD><<<grid, 256, 0, s>>>(qkv, rm, st, bq, bk, bv, cos_tab, sin_tab,           \
+                                               arena_layer, geom, n_q_heads, chunk, n_splits,      \
+                                               scale_log2, part_o, part_ml, out);                  \
   if (n_splits > 1)                                                                                \
-    attn_merge_kernel<DD><<<M * n_q_heads, DD < 64 ? 64 : DD, 0, s>>>(part_o, part_ml, rm, n_q_heads, chunk,      \
-                                                       n_splits, out);
+    attn_merge_kernel<DD><<<M * n_q_heads, DD < 64 ? 64 : DD, 0, s>>>(part_o, part_ml, rm,         \
+                                                                      n_q_heads, chunk, n_splits, out);
   switch (geom.head_dim) {
     case 32: AREAL_DEC(32) break;
     case 64: AREAL_DEC(64) break;

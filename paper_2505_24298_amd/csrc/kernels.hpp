@@ -59,12 +59,16 @@ struct AttnWork {              // prefill work item: a tile of consecutive query
   int32_t slot, row0, pos0, n_rows;   // n_rows <= attn_prefill_tile_rows()
 };
 int attn_prefill_tile_rows(int n_q_heads, int n_kv_heads);   // 16 or 32
-// decode: one query row per sequence (row i <-> rm.slot[i], rm.pos[i]); context
-// = pos+1 tokens.  `chunk` tokens per split (multiple of 128, at most 2048);
-// with n_splits > 1 the partials go through `part_o` / `part_ml` and a merge kernel.
-hipError_t launch_attn_decode(hipStream_t s, const f16* q, int M, RowMeta rm, SeqState st,
-                              const f16* arena_layer, KvGeom geom, int n_q_heads, int chunk,
-                              int n_splits, float* part_o, float* part_ml, f16* out);
+// decode: one query row per sequence (row i <-> rm.slot[i], rm.pos[i]), taken from the float32
+// QKV rows [M, (nq + 2 nkv) d] of the pass: bias, RoPE and rounding of q and of the appended
+// token's k happen inside, and the appended k, v are stored into the sequence's block
+// (table entry pos/16 must be installed).  Context = positions 0 .. pos.  `chunk` tokens per
+// split (multiple of 128, at most 2048); with n_splits > 1 the partials go through
+// `part_o` / `part_ml` and a merge kernel.
+hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
+                              const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
+                              const float* sin_tab, f16* arena_layer, KvGeom geom, int n_q_heads,
+                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out);
 hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work, int n_work,
                                SeqState st, const f16* arena_layer, KvGeom geom, int n_q_heads,
                                f16* out);

@@ -331,17 +331,19 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
       GemmW wqkv{{w.wq[l], w.wk[l], w.wv[l]}, {qd, qd + kd, qd + 2 * kd}};
       HIP_TRY(c, launch_gemm_cfg(s, xn, wqkv, qkv, a.M, qd + 2 * kd, H, qd + 2 * kd, GEMM_STORE_F32, -1, -1));
     }
-    {
-      ProfScope ps(c, AREAL_K_ROPE_KVWRITE, l, sampled, rows);
-      HIP_TRY(c, launch_rope_kvwrite(s, qkv, a.M, a.rm, st, w.has_bias ? w.bq[l] : nullptr,
-                                     w.has_bias ? w.bk[l] : nullptr, w.has_bias ? w.bv[l] : nullptr,
-                                     cos_t, sin_t, q, arena_l, c->geom, nq));
-    }
+    const f16 *bq = w.has_bias ? w.bq[l] : nullptr, *bk = w.has_bias ? w.bk[l] : nullptr,
+              *bv = w.has_bias ? w.bv[l] : nullptr;
     if (a.decode) {
+      // bias, RoPE and the store of the appended K/V are part of the attention kernel
       ProfScope ps(c, AREAL_K_ATTN_DECODE, l, sampled, a.attn_units);
-      HIP_TRY(c, launch_attn_decode(s, q, a.M, a.rm, st, arena_l, c->geom, nq, a.chunk, a.n_splits,
-                                    c->wsp<float>(c->lay.part_o), c->wsp<float>(c->lay.part_ml), attn));
+      HIP_TRY(c, launch_attn_decode(s, qkv, a.M, a.rm, st, bq, bk, bv, cos_t, sin_t, arena_l, c->geom, nq,
+                                    a.chunk, a.n_splits, c->wsp<float>(c->lay.part_o),
+                                    c->wsp<float>(c->lay.part_ml), attn));
     } else {
+      {
+        ProfScope ps(c, AREAL_K_ROPE_KVWRITE, l, sampled, rows);
+        HIP_TRY(c, launch_rope_kvwrite(s, qkv, a.M, a.rm, st, bq, bk, bv, cos_t, sin_t, q, arena_l, c->geom, nq));
+      }
       ProfScope ps(c, AREAL_K_ATTN_PREFILL, l, sampled, a.attn_units);
       HIP_TRY(c, launch_attn_prefill(s, q, a.work, a.n_work, st, arena_l, c->geom, nq, attn));
     }
@@ -545,6 +547,10 @@ int areal_create(const areal_model_cfg* cfg, areal_ctx** out) {
     e = hipEventCreateWithFlags(&c->seg_done[i], hipEventDisableTiming);
     if (e != hipSuccess) { c->seg_done[i] = nullptr; return die(e, "hipEventCreate"); }
   }
+  // Masked positions of a partly filled block still pass through the value product
+  // with weight 0: the pool must never hold NaN or Inf bit patterns.
+  e = hipMemsetAsync(cfg->kv_arena, 0, (size_t)c->n_blocks * blk, c->stream);
+  if (e != hipSuccess) return die(e, "hipMemsetAsync(kv_arena)");
   // rotary tables: angle = pos * theta^(-2j/d), evaluated in double
   {
     const int half = cfg->head_dim / 2;
