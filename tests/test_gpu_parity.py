@@ -184,3 +184,28 @@ def test_errors_leave_state_unchanged(torch, binding):
     eng.free_seq(0)
     assert eng.kv_blocks() == (3, 3)
     eng.close()
+
+
+def test_tiny_deep_context_many_splits(torch, binding):
+    """One sequence of 8,300 tokens on the tiny shape: 33 splits of 256 tokens
+    would exceed the split limit, so the launch takes longer splits; prefill runs
+    in many passes over one long sequence."""
+    from oracle import decoder
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 17)
+    rng = np.random.default_rng(18)
+    T = 8300
+    prompt = rng.integers(0, cfg["vocab"], size=T).astype(np.int32)
+    nxt = rng.integers(0, cfg["vocab"], size=3).astype(np.int32)
+    eng = binding.Areal(cfg, max_seqs=1, max_seq_len=T + 8, max_batch_tokens=1024, kv_blocks=T // 16 + 4,
+                        convert_weights=True)
+    eng.load_weights(binding.weights_to_device(w, bf16=False), 0)
+    got = [eng.prefill([0], [prompt]).cpu().numpy()[0]]
+    for t in range(3):
+        got.append(eng.decode_step([0], torch.from_numpy(nxt[t:t + 1].copy()).cuda()).cpu().numpy()[0])
+    eng.close()
+    seq = np.concatenate([prompt, nxt])
+    ref = decoder.forward(seq, _f16_weights(w), cfg, rows=[T - 1, T, T + 1, T + 2])
+    worst = max(float(np.abs(g - r).max()) for g, r in zip(got, ref))
+    print(f"tiny/deep: logits {worst:.2e}")
+    assert worst <= LOGIT_TOL

@@ -128,3 +128,45 @@ def test_qwen2_7b_dimensions_four_layers_top_p():
     eng.close()
     print(f"7B dims x4 layers: logits {worst_logit:.2e}  logp_behav {worst_lb:.2e}  logp_full {worst_lf:.2e}")
     assert worst_logit <= LOGIT_TOL and worst_lb <= LOGP_TOL and worst_lf <= LOGP_TOL
+
+
+def test_bench_launch_configuration_sampled_sequences():
+    """The launch configuration bench.py times: all 256 sequences of the
+    qwen2-1.5b-rollout workload, prefill in passes of 8192 rows (large-tile GEMMs,
+    shared-KV prefill attention), decode at 256 rows per pass.  The oracle
+    recomputes three sampled sequences one by one: logits after the prompt and
+    after each of two forced decode steps."""
+    import torch
+    from bench import device_weights
+    from oracle import decoder
+    from paper_2505_24298_amd import binding
+    cfg, wl, prompts, out_lens = synth.make_workload("qwen2-1.5b-rollout")
+    n = len(prompts)
+    assert n == 256
+    n_new = 2
+    w0 = device_weights(torch, cfg, 0, "cuda:0")
+    forced = np.random.default_rng(41).integers(0, cfg["vocab"], size=(n, n_new)).astype(np.int32)
+    eng = binding.Areal(cfg, max_seqs=n, max_seq_len=512 + n_new + 1, max_batch_tokens=8192,
+                        kv_blocks=sum(len(p) + n_new for p in prompts) // 16 + 2 * n)
+    eng.load_weights(w0, 0)
+    ids = list(range(n))
+    lens = np.array([len(p) for p in prompts])
+    sample = [int(np.argmin(lens)), 100, 255]             # shortest prompt, one mid-batch, the last row
+    logits = eng.prefill(ids, prompts)
+    idx = torch.tensor(sample, device="cuda")
+    got = [logits[idx].cpu().numpy()]
+    for t in range(n_new):
+        toks = torch.from_numpy(forced[:, t].copy()).cuda()
+        logits = eng.decode_step(ids, toks)
+        got.append(logits[idx].cpu().numpy())
+    eng.close()
+    wo = _to_oracle(w0)
+    worst = 0.0
+    for k, s in enumerate(sample):
+        seq = np.concatenate([prompts[s], forced[s]])
+        rows = [len(prompts[s]) - 1 + t for t in range(n_new + 1)]
+        ref = decoder.forward(seq, wo, cfg, rows=rows)
+        for t in range(n_new + 1):
+            worst = max(worst, float(np.abs(got[t][k] - ref[t]).max()))
+    print(f"bench configuration, 3 sampled sequences: logits {worst:.2e}")
+    assert worst <= LOGIT_TOL

@@ -153,3 +153,15 @@ def test_planner_covers_every_position_once_in_order(L):
         assert all(v <= max_rows for v in rows_in_pass.values())
         assert all(v == max_rows for k, v in rows_in_pass.items() if k != max(rows_in_pass))
         assert list(rec[:, 0]) == sorted(rec[:, 0]) and list(rec[:, 1]) == sorted(rec[:, 1])
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box has one GPU: bench.py --gpus N with N > 1 exits with a message
+    before it touches the device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one MI355X" in r.stderr and r.stdout.strip() == ""
