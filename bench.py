@@ -167,6 +167,92 @@ def rollout(eng, torch, cfg, prompts, out_lens, temperature, top_p, seed, interr
     return res
 
 
+def streaming_rollout(eng, torch, cfg, lib, prompts, out_lens, slots, train_batch, eta, weight_sets,
+                      temperature, top_p, seed):
+    """The paper's streaming regime on one GPU (Sections 4.1, 5.1): `slots`
+    sequences decode together; a finished sequence's slot is refilled with the
+    next prompt as long as the staleness gate floor((N_r-1)/B) <= i + eta admits
+    it; every `train_batch` finished trajectories the (simulated) trainer
+    publishes a new version, which interrupts the generation in flight
+    (areal_update_weights_interrupt: all prefixes recomputed).  eta = 0 is the
+    synchronous schedule.  Returns timings and counters."""
+    n_total = len(prompts)
+    dev = eng.device
+    V = cfg["vocab"]
+    logits = torch.empty((slots, V), dtype=torch.float32, device=dev)
+    logits_b = torch.empty_like(logits)
+    toks = torch.empty(slots, dtype=torch.int32, device=dev)
+    lb = torch.empty(slots, dtype=torch.float32, device=dev)
+    lf = torch.empty(slots, dtype=torch.float32, device=dev)
+    gate = lib.areal_gate_create(train_batch, eta)
+    free_ids = list(range(slots - 1, -1, -1))
+    ids = np.zeros(0, dtype=np.int32)          # live sequences, row order
+    pos = np.zeros(0, dtype=np.int64)          # current length = position of the next token
+    remaining = np.zeros(0, dtype=np.int64)
+    nxt = finished = version = steps = interrupts = retok_total = 0
+    gen_tokens = 0
+    rows_sum = 0
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    e0, e1 = ev(), ev()
+    torch.cuda.synchronize()
+    e0.record()
+
+    def admit(n_have):
+        nonlocal nxt, ids, pos, remaining
+        want = min(len(free_ids), n_total - nxt)
+        k = int(lib.areal_gate_submit(gate, want)) if want > 0 else 0
+        if k == 0:
+            return
+        new_ids = [free_ids.pop() for _ in range(k)]
+        new_prompts = prompts[nxt:nxt + k]
+        eng.prefill(new_ids, new_prompts, logits_out=logits[n_have:n_have + k])
+        ids = np.concatenate([ids, np.asarray(new_ids, dtype=np.int32)])
+        pos = np.concatenate([pos, np.asarray([len(p) for p in new_prompts], dtype=np.int64)])
+        remaining = np.concatenate([remaining, np.asarray(out_lens[nxt:nxt + k], dtype=np.int64)])
+        nxt += k
+
+    admit(0)
+    while finished < n_total:
+        n = len(ids)
+        assert n > 0, "gate closed with nothing in flight"
+        eng.sample_logprob(logits[:n], ids, pos, temperature, top_p, seed, out=(toks[:n], lb[:n], lf[:n]))
+        gen_tokens += n
+        remaining -= 1
+        keep = remaining > 0
+        tk = toks[:n]
+        if not keep.all():
+            for s in ids[~keep]:
+                eng.free_seq(int(s))
+                free_ids.append(int(s))
+            finished += int((~keep).sum())
+            tk = tk[torch.from_numpy(np.nonzero(keep)[0]).to(dev)]      # row compaction (bookkeeping)
+            ids, pos, remaining = ids[keep], pos[keep], remaining[keep]
+        n_keep = len(ids)
+        if n_keep:
+            eng.decode_step(ids, tk.contiguous(), logits_out=logits[:n_keep])
+            pos = pos + 1
+            steps += 1
+            rows_sum += n_keep
+        if finished // train_batch > version:                 # the trainer has stepped
+            version = finished // train_batch
+            lib.areal_gate_set_version(gate, version)
+            live, _, retok = eng.update_weights_interrupt(weight_sets[version % len(weight_sets)], version,
+                                                          logits_out=logits_b)
+            interrupts += 1
+            retok_total += retok
+            if len(live):                                     # logits now come in ascending id order
+                order = np.argsort(ids, kind="stable")
+                assert ids[order].tolist() == live.tolist()
+                ids, pos, remaining = ids[order], pos[order], remaining[order]
+                logits, logits_b = logits_b, logits
+        admit(n_keep)
+    e1.record()
+    torch.cuda.synchronize()
+    lib.areal_gate_destroy(gate)
+    return dict(total_ms=e0.elapsed_time(e1), gen_tokens=gen_tokens, decode_steps=steps,
+                mean_rows=rows_sum / max(steps, 1), interrupts=interrupts, reprefill_tokens=retok_total)
+
+
 def cpu_oracle_baseline(cfg_name, budget_s=20.0):
     """The CPU oracle as it stands (incremental-KV variant, numpy float64) on a
     bounded slice of the same workload: 2 sequences of the workload's model
@@ -248,6 +334,42 @@ def depth_sweep(args):
         torch.cuda.empty_cache()
 
 
+def streaming(args):
+    import torch
+    from paper_2505_24298_amd import binding, synth
+    dev = "cuda:0"
+    wl = dict(synth.WORKLOADS[args.workload])
+    cfg = synth.shape(wl["shape"])
+    n_total, slots = args.streaming, wl["n_prompts"] * wl["samples"]
+    assert n_total % wl["samples"] == 0
+    prompts = synth.make_prompts(cfg, n_total // wl["samples"], wl["samples"], wl["len_lo"], wl["len_hi"],
+                                 wl["seed"] + 1)
+    outs = synth.output_lengths(n_total, wl["out_median"], wl["out_sigma"], wl["out_cap"], wl["seed"] + 2)
+    if args.scale_out != 1.0:
+        outs = np.maximum(1, np.rint(outs * args.scale_out)).astype(np.int64)
+    max_len = wl["len_hi"] + int(outs.max()) + 1
+    eng = binding.Areal(cfg, max_seqs=slots, max_seq_len=max_len, max_batch_tokens=args.max_batch_tokens,
+                        kv_blocks=slots * (max_len // 16 + 2))
+    w0 = device_weights(torch, cfg, 0, dev)
+    weight_sets = [w0, device_weights(torch, cfg, 1001, dev, base=w0, scale=1e-3)]
+    eng.load_weights(w0, 0)
+    rollout(eng, torch, cfg, prompts[:2], [3, 3], wl["temperature"], wl["top_p"], 0)      # loads the code objects
+    eng.load_weights(w0, 0)
+    r = streaming_rollout(eng, torch, cfg, binding.lib(), prompts, outs, slots, args.train_batch, args.eta,
+                          weight_sets, wl["temperature"], wl["top_p"], 0)
+    out = {"metric": "gen tokens/s, 1 MI355X, streaming rollout with staleness gate", "unit": "tokens/s",
+           "value": round(r["gen_tokens"] / (r["total_ms"] * 1e-3), 1), "n_gpus": 1,
+           "ms_total": round(r["total_ms"], 1), "dtype": "f16", "data": "synthetic",
+           "config": {"workload": args.workload + f" streamed: {n_total} trajectories through {slots} slots, "
+                      f"training batch {args.train_batch}, eta {args.eta}"
+                      + (f", x{args.scale_out} output length" if args.scale_out != 1 else "")},
+           "generated_tokens": r["gen_tokens"], "decode_steps": r["decode_steps"],
+           "mean_rows_per_step": round(r["mean_rows"], 1), "weight_updates": r["interrupts"],
+           "reprefilled_tokens": r["reprefill_tokens"]}
+    eng.close()
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -264,6 +386,11 @@ def main():
     ap.add_argument("--depth-sweep", default="", help="comma-separated context depths: time decode steps at "
                     "each depth (deep-context workload) instead of the rollout")
     ap.add_argument("--sweep-steps", type=int, default=32)
+    ap.add_argument("--streaming", type=int, default=0, help="streaming regime: total trajectories "
+                    "(multiple of 16), slots refilled as sequences finish, staleness gate, weight "
+                    "update + interrupt every --train-batch finished trajectories")
+    ap.add_argument("--eta", type=int, default=4, help="maximum staleness for --streaming (0 = synchronous)")
+    ap.add_argument("--train-batch", type=int, default=256)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one MI355X: this build has no multi-GPU path (--gpus must be 1)",
@@ -275,6 +402,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     if args.depth_sweep:
         depth_sweep(args)
+        return
+    if args.streaming:
+        streaming(args)
         return
     dev = "cuda:0"
     cfg, wl, prompts, out_lens = synth.make_workload(args.workload, scale_out=args.scale_out)

@@ -1,7 +1,7 @@
 /*
  * areal_host.h -- host-only entry points of the library: the paged KV block
- * allocator and the pass planner, exposed so that they can be exercised
- * without a GPU.  They are the same objects the generation calls of areal.h
+ * allocator, the pass planner and the staleness gate of the rollout
+ * controller, exposed so that they can be exercised without a GPU.  They are the same objects the generation calls of areal.h
  * use internally (KV cache management is named by the paper, Section 2 "LLM
  * Training and Inference", as a requirement of generation; the token budget
  * per pass follows the padding-free packing of Section 6).
@@ -40,6 +40,22 @@ void areal_kvalloc_shuffle(areal_kvalloc* a, uint64_t seed);
  * that ends a span, else -1. */
 int32_t areal_plan_passes(int32_t n_spans, const int32_t* lens, int32_t max_rows, int32_t* out,
                           int32_t cap);
+
+/* Section 5.1 (staleness-aware training): the rollout controller submits the
+ * N-th generation request only if floor((N-1)/B) <= i + eta, with B the
+ * training batch size, i the current policy version and eta the maximum
+ * staleness of a training batch (eta = 0: synchronous).  The gate counts the
+ * requests it has admitted (N_r) and holds the version it was last told.
+ * create: NULL unless batch_size >= 1 and eta >= 0.  submit: tries n more
+ * requests, returns how many it admitted (0 .. n).  set_version: versions only
+ * grow; AREAL_E_STATE otherwise. */
+typedef struct areal_gate areal_gate;
+areal_gate* areal_gate_create(int64_t batch_size, int64_t eta);
+void areal_gate_destroy(areal_gate* g);
+int64_t areal_gate_submit(areal_gate* g, int64_t n);
+int64_t areal_gate_budget(const areal_gate* g);      /* requests admissible right now */
+int areal_gate_set_version(areal_gate* g, int64_t version);
+int64_t areal_gate_submitted(const areal_gate* g);   /* N_r */
 
 #ifdef __cplusplus
 }

@@ -66,6 +66,12 @@ _SIGNATURES = {
                                        C.c_void_p]),
     "areal_update_weights_interrupt": (C.c_int, [C.c_void_p, C.POINTER(Weights), C.c_uint64, _I32P,
                                                  _I32P, C.c_void_p, _I64P]),
+    "areal_gate_create": (C.c_void_p, [C.c_int64, C.c_int64]),
+    "areal_gate_destroy": (None, [C.c_void_p]),
+    "areal_gate_submit": (C.c_int64, [C.c_void_p, C.c_int64]),
+    "areal_gate_budget": (C.c_int64, [C.c_void_p]),
+    "areal_gate_set_version": (C.c_int, [C.c_void_p, C.c_int64]),
+    "areal_gate_submitted": (C.c_int64, [C.c_void_p]),
     "areal_recompute_logprob": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_float, C.c_void_p,
                                           C.c_int32, C.c_void_p]),
     "areal_free_seq": (C.c_int, [C.c_void_p, C.c_int32]),

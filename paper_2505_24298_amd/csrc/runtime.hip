@@ -14,6 +14,7 @@
 #include "../../include/areal_ops.h"
 #include "kernels.hpp"
 #include "kv_alloc.hpp"
+#include "gate.hpp"
 
 using namespace areal;
 
@@ -942,6 +943,20 @@ int32_t areal_kvalloc_table(const areal_kvalloc* a, int32_t seq, int32_t* out, i
   return (int32_t)b.size();
 }
 void areal_kvalloc_shuffle(areal_kvalloc* a, uint64_t seed) { a->a.shuffle_free(seed); }
+
+struct areal_gate { StalenessGate g; };
+areal_gate* areal_gate_create(int64_t batch_size, int64_t eta) {
+  if (batch_size < 1 || eta < 0) return nullptr;
+  return new areal_gate{StalenessGate(batch_size, eta)};
+}
+void areal_gate_destroy(areal_gate* g) { delete g; }
+int64_t areal_gate_submit(areal_gate* g, int64_t n) { return g ? g->g.submit(n) : 0; }
+int64_t areal_gate_budget(const areal_gate* g) { return g ? g->g.budget() : 0; }
+int areal_gate_set_version(areal_gate* g, int64_t version) {
+  if (!g) return AREAL_E_INVAL;
+  return g->g.set_version(version) ? AREAL_OK : AREAL_E_STATE;
+}
+int64_t areal_gate_submitted(const areal_gate* g) { return g ? g->g.submitted() : 0; }
 
 int32_t areal_plan_passes(int32_t n_spans, const int32_t* lens, int32_t max_rows, int32_t* out, int32_t cap) {
   std::vector<Span> spans;

@@ -165,3 +165,37 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "one MI355X" in r.stderr and r.stdout.strip() == ""
+
+
+def test_staleness_gate_matches_oracle_request_by_request():
+    """The library's gate (budget form) against the oracle that applies the
+    paper's inequality one request at a time, over random interleavings of
+    submissions and version bumps, for every small (B, eta)."""
+    from oracle import staleness
+    L = binding.lib()
+    rng = np.random.default_rng(3)
+    for B in (1, 2, 5, 16):
+        for eta in (0, 1, 4):
+            g = L.areal_gate_create(B, eta)
+            o = staleness.StalenessGate(B, eta)
+            v = 0
+            for _ in range(200):
+                if rng.random() < 0.3:
+                    v += int(rng.integers(0, 3))
+                    assert L.areal_gate_set_version(g, v) == 0
+                    o.set_version(v)
+                n = int(rng.integers(0, 3 * B))
+                assert L.areal_gate_budget(g) == _budget(o)
+                assert L.areal_gate_submit(g, n) == o.submit(n)
+                assert L.areal_gate_submitted(g) == o.submitted
+            assert L.areal_gate_set_version(g, v - 1) == binding.E_STATE if v > 0 else True
+            L.areal_gate_destroy(g)
+    assert not L.areal_gate_create(0, 1) and not L.areal_gate_create(4, -1)
+
+
+def _budget(o):
+    """How many requests the oracle gate would admit now (on a copy)."""
+    from oracle import staleness
+    c = staleness.StalenessGate(o.B, o.eta, o.version)
+    c.submitted = o.submitted
+    return c.submit(10 ** 6)
