@@ -13,6 +13,7 @@
 //                                       B-operand layout, so nothing is
 //                                       transposed or staged through LDS.
 #include "kernels.hpp"
+#include <type_traits>
 
 namespace areal {
 namespace {
@@ -387,52 +388,76 @@ struct PairFrag {
   f16x8 v[2][D / 32];
 };
 
-template <int D>
-__device__ __forceinline__ void attend_pair(const PairFrag<D>& f, const f16x8 (&qf)[D / 32], int b,
-                                            int row_pos, float scale_log2, float& m, float& l,
-                                            f32x4 (&o)[D / 16], int lane) {
+// One online-softmax update of all RGW row-groups of a wave over the two blocks
+// in `f`.  The three phases run over all row-groups at a time, so that their
+// independent MFMA chains and reductions overlap and the value operands are
+// assembled once.  The running maximum is a reference, not an exact maximum: it
+// is raised (two cross-lane exchanges and a rescale of the accumulator) only
+// when some score of the wave exceeds it by more than 2^kMaxSlack, so
+// probabilities stay below 2^kMaxSlack in half precision and the common step
+// has no cross-lane traffic at all.
+constexpr float kMaxSlack = 8.0f;
+
+template <int D, int RGW, bool MASK>
+__device__ __forceinline__ void attend_pairs(const PairFrag<D>& f, const f16x8 (&qf)[RGW][D / 32], int b,
+                                             const int (&rpos)[RGW], float scale_log2, float (&m)[RGW],
+                                             float (&l)[RGW], f32x4 (&o)[RGW][D / 16], int lane) {
   const int g = lane >> 4;
-  float s[2][4];
-  float mx = -INFINITY;
+  f32x4 acc[RGW][2];
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int r = 0; r < RGW; ++r)
 #pragma unroll
-    for (int c = 0; c < D / 32; ++c) acc = mfma_qk(f.k[u][c], qf[c], acc);
+    for (int u = 0; u < 2; ++u) acc[r][u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int t = (b + u) * kBlockTokens + 4 * g + v;
-      s[u][v] = t <= row_pos ? acc[v] * scale_log2 : -INFINITY;
-      mx = fmaxf(mx, s[u][v]);
+  for (int c = 0; c < D / 32; ++c)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int r = 0; r < RGW; ++r) acc[r][u] = mfma_qk(f.k[u][c], qf[r][c], acc[r][u]);
+
+  // scores stay unscaled (s = q.k); the 1/sqrt(d) log2(e) factor rides in the exponent's fma.
+  // MASK = false: every token of the pair is visible to every row of the wave.
+  f16x8 p[RGW];
+#pragma unroll
+  for (int r = 0; r < RGW; ++r) {
+    float s[2][4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int t = (b + u) * kBlockTokens + 4 * g + v;
+        s[u][v] = (!MASK || t <= rpos[r]) ? acc[r][u][v] : -INFINITY;
+        mx = fmaxf(mx, s[u][v]);
+      }
+    mx *= scale_log2;
+    if (__any(mx > m[r] + kMaxSlack)) {                 // wave-uniform; m = -inf at the start
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m[r], mx);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m[r] - m_use);   // m = -inf -> 0
+      m[r] = m_new;
+      l[r] *= alpha;
+      float ao[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) ao[v] = __shfl(alpha, 4 * g + v);
+#pragma unroll
+      for (int n = 0; n < D / 16; ++n)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) o[r][n][v] *= ao[v];
     }
-  }
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(m, mx);
-  const float m_use = m_new == -INFINITY ? 0.f : m_new;
-  const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-  m = m_new;
-  float psum = 0.f;
-  f16x8 p;
+    const float m_use = m[r] == -INFINITY ? 0.f : m[r];
+    float psum = 0.f;
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const float e = __builtin_amdgcn_exp2f(s[u][v] - m_use);
-      psum += e;
-      p[u * 4 + v] = f2h(e);
-    }
-  l = l * alpha + psum;
-  // the running maximum settles after a few blocks: rescale the accumulator only
-  // when some row of the wave actually moved (wave-uniform branch)
-  if (__any(alpha != 1.0f)) {
-    float ao[4];
-#pragma unroll
-    for (int v = 0; v < 4; ++v) ao[v] = __shfl(alpha, 4 * g + v);
-#pragma unroll
-    for (int n = 0; n < D / 16; ++n)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) o[n][v] *= ao[v];
+      for (int v = 0; v < 4; ++v) {
+        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[u][v], scale_log2, -m_use));
+        psum += e;
+        p[r][u * 4 + v] = f2h(e);
+      }
+    l[r] += psum;
   }
 #pragma unroll
   for (int n = 0; n < D / 16; ++n) {
@@ -440,12 +465,13 @@ __device__ __forceinline__ void attend_pair(const PairFrag<D>& f, const f16x8 (&
     f16x8 vb;
     if (n & 1) vb = f16x8{v0[4], v0[5], v0[6], v0[7], v1[4], v1[5], v1[6], v1[7]};
     else vb = f16x8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-    o[n] = mfma_qk(p, vb, o[n]);
+#pragma unroll
+    for (int r = 0; r < RGW; ++r) o[r][n] = mfma_qk(p[r], vb, o[r][n]);
   }
 }
 
 template <int D, int RGW>
-__global__ __launch_bounds__(256) void attn_prefill_kernel(
+__global__ __launch_bounds__(256, (D == 128 && RGW == 3) ? 2 : 1) void attn_prefill_kernel(
     const f16* __restrict__ q, const AttnWork* __restrict__ work, SeqState st,
     const f16* __restrict__ arena, KvGeom geom, int nq, int tile_pos, float scale_log2,
     f16* __restrict__ out) {
@@ -491,6 +517,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
     for (int n = 0; n < D / 16; ++n) o[r][n] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  // pairs of blocks that lie wholly below the first query position of this wave need no mask
+  // (row-group r = 0 holds the wave's earliest positions; a wave without rows masks everything)
+  const int p_free = gmax[0] >= 0 ? (wk.pos0 + ((wave * RGW) / G) * 16 + 1) / (2 * kBlockTokens) : 0;
+
   // ---- this wave's share of the loads: one tile of the stage (block u, K or V) ----
   const int u_ld = wave >> 1, isv_ld = wave & 1;
   int src_off[NI];
@@ -531,7 +561,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
 
 #pragma unroll
   for (int s = 0; s < PF_STAGES - 1; ++s) issue(min(s, n_pairs - 1), s);
-  for (int p = 0; p < n_pairs; ++p) {
+  auto step = [&](int p, auto masked) {
     wait_vmcnt((PF_STAGES - 2) * NI);
     __builtin_amdgcn_s_barrier();
     issue(min(p + PF_STAGES - 1, n_pairs - 1), (p + PF_STAGES - 1) % PF_STAGES);
@@ -544,11 +574,13 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(
         f.k[u][c] = *reinterpret_cast<const f16x8*>(base + (u * 2) * TILE_B + k_off[c]);
         f.v[u][c] = *reinterpret_cast<const f16x8*>(base + (u * 2 + 1) * TILE_B + v_off[c]);
       }
-#pragma unroll
-    for (int r = 0; r < RGW; ++r)
-      if (gmax[r] >= 2 * p * kBlockTokens)             // wave-uniform: the row-group sees this pair
-        attend_pair<D>(f, qf[r], 2 * p, rpos[r], scale_log2, m[r], l[r], o[r], lane);
-  }
+    attend_pairs<D, RGW, decltype(masked)::value>(f, qf, 2 * p, rpos, scale_log2, m, l, o, lane);
+  };
+  // all waves of the work-group run the same number of steps (the barrier is shared); each
+  // wave's mask-free prefix is its own
+  const int p_split = min(p_free, n_pairs);
+  for (int p = 0; p < p_split; ++p) step(p, std::false_type{});
+  for (int p = p_split; p < n_pairs; ++p) step(p, std::true_type{});
   wait_vmcnt(0);
 
 #pragma unroll
