@@ -382,11 +382,6 @@ __global__ __launch_bounds__(D < 64 ? 64 : D) void attn_merge_kernel(const float
 // the stored V tiles already have.
 constexpr int PF_STAGES = 3;
 
-template <int D>
-struct PairFrag {
-  f16x8 k[2][D / 32];
-  f16x8 v[2][D / 32];
-};
 
 // One online-softmax update of all RGW row-groups of a wave over the two blocks
 // in `f`.  The three phases run over all row-groups at a time, so that their
@@ -399,10 +394,21 @@ struct PairFrag {
 constexpr float kMaxSlack = 8.0f;
 
 template <int D, int RGW, bool MASK>
-__device__ __forceinline__ void attend_pairs(const PairFrag<D>& f, const f16x8 (&qf)[RGW][D / 32], int b,
-                                             const int (&rpos)[RGW], float scale_log2, float (&m)[RGW],
-                                             float (&l)[RGW], f32x4 (&o)[RGW][D / 16], int lane) {
+__device__ __forceinline__ void attend_pairs(const char* __restrict__ stage, const int (&k_off)[D / 32],
+                                             const int (&v_off)[D / 32], const f16x8 (&qf)[RGW][D / 32],
+                                             int b, const int (&rpos)[RGW], float scale_log2,
+                                             float (&m)[RGW], float (&l)[RGW], f32x4 (&o)[RGW][D / 16],
+                                             int lane) {
+  constexpr int TILE_B = 16 * D * 2;
   const int g = lane >> 4;
+  // K fragments now, V fragments only once the probabilities exist: the two sets never
+  // occupy registers together
+  f16x8 kf[2][D / 32];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c)
+      kf[u][c] = *reinterpret_cast<const f16x8*>(stage + (u * 2) * TILE_B + k_off[c]);
   f32x4 acc[RGW][2];
 #pragma unroll
   for (int r = 0; r < RGW; ++r)
@@ -413,7 +419,7 @@ __device__ __forceinline__ void attend_pairs(const PairFrag<D>& f, const f16x8 (
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int r = 0; r < RGW; ++r) acc[r][u] = mfma_qk(f.k[u][c], qf[r][c], acc[r][u]);
+      for (int r = 0; r < RGW; ++r) acc[r][u] = mfma_qk(kf[u][c], qf[r][c], acc[r][u]);
 
   // scores stay unscaled (s = q.k); the 1/sqrt(d) log2(e) factor rides in the exponent's fma.
   // MASK = false: every token of the pair is visible to every row of the wave.
@@ -459,14 +465,17 @@ __device__ __forceinline__ void attend_pairs(const PairFrag<D>& f, const f16x8 (
       }
     l[r] += psum;
   }
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int n = 0; n < D / 16; ++n) {
-    const f16x8 v0 = f.v[0][n >> 1], v1 = f.v[1][n >> 1];
-    f16x8 vb;
-    if (n & 1) vb = f16x8{v0[4], v0[5], v0[6], v0[7], v1[4], v1[5], v1[6], v1[7]};
-    else vb = f16x8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+  for (int c = 0; c < D / 32; ++c) {
+    const f16x8 v0 = *reinterpret_cast<const f16x8*>(stage + 1 * TILE_B + v_off[c]);
+    const f16x8 v1 = *reinterpret_cast<const f16x8*>(stage + 3 * TILE_B + v_off[c]);
+    const f16x8 ve = f16x8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+    const f16x8 vo = f16x8{v0[4], v0[5], v0[6], v0[7], v1[4], v1[5], v1[6], v1[7]};
 #pragma unroll
-    for (int r = 0; r < RGW; ++r) o[r][n] = mfma_qk(p[r], vb, o[r][n]);
+    for (int r = 0; r < RGW; ++r) o[r][2 * c] = mfma_qk(p[r], ve, o[r][2 * c]);
+#pragma unroll
+    for (int r = 0; r < RGW; ++r) o[r][2 * c + 1] = mfma_qk(p[r], vo, o[r][2 * c + 1]);
   }
 }
 
@@ -475,8 +484,6 @@ __global__ __launch_bounds__(256, (D == 128 && RGW == 3) ? 2 : 1) void attn_pref
     const f16* __restrict__ q, const AttnWork* __restrict__ work, SeqState st,
     const f16* __restrict__ arena, KvGeom geom, int nq, int tile_pos, float scale_log2,
     f16* __restrict__ out) {
-  constexpr int CPR = D / 8;              // 16-byte chunks per K row
-  constexpr int NCH = D / 32;             // 16-byte chunks per lane of a V tile
   constexpr int TILE_B = 16 * D * 2;      // bytes of one K or V tile
   constexpr int STAGE_B = 4 * TILE_B;     // two blocks x (K, V)
   constexpr int NI = TILE_B / 1024;       // load instructions per tile = per wave per stage
@@ -508,9 +515,10 @@ __global__ __launch_bounds__(256, (D == 128 && RGW == 3) ? 2 : 1) void attn_pref
     gmax[r] = active ? wk.pos0 + min(wk.n_rows, pos_blk * 16 + 16) - 1 : -1;
     rpos[r] = ok ? wk.pos0 + row_in : gmax[r];
     const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const f16* qp = q + ((int64_t)(wk.row0 + (ok ? row_in : 0)) * nq + (active ? head : 0)) * D + g * (D / 4);
+    // MFMA c contracts dims [32c, 32c+32), lane group g its slice [32c + 8g, +8): the order of the K tiles
+    const f16* qp = q + ((int64_t)(wk.row0 + (ok ? row_in : 0)) * nq + (active ? head : 0)) * D + g * 8;
 #pragma unroll
-    for (int c = 0; c < D / 32; ++c) qf[r][c] = ok ? ld8(qp + c * 8) : zero8;
+    for (int c = 0; c < D / 32; ++c) qf[r][c] = ok ? ld8(qp + c * 32) : zero8;
     m[r] = -INFINITY;
     l[r] = 0.f;
 #pragma unroll
@@ -523,18 +531,11 @@ __global__ __launch_bounds__(256, (D == 128 && RGW == 3) ? 2 : 1) void attn_pref
 
   // ---- this wave's share of the loads: one tile of the stage (block u, K or V) ----
   const int u_ld = wave >> 1, isv_ld = wave & 1;
+  // tiles are stored in operand order, chunk c of all lanes in a 1 KiB run: the copy into LDS
+  // is verbatim and lane-linear, and so are the fragment reads (no bank conflicts, no swizzle)
   int src_off[NI];
 #pragma unroll
-  for (int t = 0; t < NI; ++t) {
-    const int slot = t * 64 + lane;
-    if (!isv_ld) {                                   // K: slot (row, chunk ^ row) <- chunk of that row
-      const int row = slot / CPR, c = (slot % CPR) ^ (row & (CPR - 1));
-      src_off[t] = k_tile_index(row, c * 8);
-    } else {                                         // V: slot (lane, i ^ f(lane)) <- chunk i of that lane
-      const int ln = slot / NCH, i = (slot % NCH) ^ ((ln >> 2) & (NCH - 1));
-      src_off[t] = (i * 64 + ln) * 8;
-    }
-  }
+  for (int t = 0; t < NI; ++t) src_off[t] = (t * 64 + lane) * 8;
   int id_chunk = -1, ids = 0;
   auto issue = [&](int pair, int stage) {
     const int b = min(2 * pair + u_ld, b_end - 1);     // past the end: re-read the last block (masked anyway)
@@ -553,11 +554,7 @@ __global__ __launch_bounds__(256, (D == 128 && RGW == 3) ? 2 : 1) void attn_pref
   // ---- fragment addresses inside a stage ----
   int k_off[D / 32], v_off[D / 32];
 #pragma unroll
-  for (int c = 0; c < D / 32; ++c) {
-    const int cc = g * NCH + c;
-    k_off[c] = (j * CPR + (cc ^ (j & (CPR - 1)))) * 16;
-    v_off[c] = (lane * NCH + (c ^ ((lane >> 2) & (NCH - 1)))) * 16;
-  }
+  for (int c = 0; c < D / 32; ++c) k_off[c] = v_off[c] = c * 1024 + lane * 16;
 
 #pragma unroll
   for (int s = 0; s < PF_STAGES - 1; ++s) issue(min(s, n_pairs - 1), s);
@@ -565,16 +562,8 @@ __global__ __launch_bounds__(256, (D == 128 && RGW == 3) ? 2 : 1) void attn_pref
     wait_vmcnt((PF_STAGES - 2) * NI);
     __builtin_amdgcn_s_barrier();
     issue(min(p + PF_STAGES - 1, n_pairs - 1), (p + PF_STAGES - 1) % PF_STAGES);
-    const char* base = lds + (p % PF_STAGES) * STAGE_B;
-    PairFrag<D> f;
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int c = 0; c < D / 32; ++c) {
-        f.k[u][c] = *reinterpret_cast<const f16x8*>(base + (u * 2) * TILE_B + k_off[c]);
-        f.v[u][c] = *reinterpret_cast<const f16x8*>(base + (u * 2 + 1) * TILE_B + v_off[c]);
-      }
-    attend_pairs<D, RGW, decltype(masked)::value>(f, qf, 2 * p, rpos, scale_log2, m, l, o, lane);
+    attend_pairs<D, RGW, decltype(masked)::value>(lds + (p % PF_STAGES) * STAGE_B, k_off, v_off, qf, 2 * p,
+                                                  rpos, scale_log2, m, l, o, lane);
   };
   // all waves of the work-group run the same number of steps (the barrier is shared); each
   // wave's mask-free prefix is its own
