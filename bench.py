@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 / bf16
 # HBM bytes the decode attention kernel moves per algorithmic K/V byte, from rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs calibrated with a plain copy (profiles/attn_decode_kernel_hbm_traffic.md)
-ATTN_DECODE_FETCH_OVER_ALGORITHMIC = 1.014
-ATTN_DECODE_WRITE_OVER_ALGORITHMIC = 0.023
+ATTN_DECODE_FETCH_OVER_ALGORITHMIC = 1.024
+ATTN_DECODE_WRITE_OVER_ALGORITHMIC = 0.028
 
 
 def device_weights(torch, cfg, seed, device, base=None, scale=None):

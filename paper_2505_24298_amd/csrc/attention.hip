@@ -13,6 +13,7 @@
 //                                       B-operand layout, so nothing is
 //                                       transposed or staged through LDS.
 #include "kernels.hpp"
+#include <cstdlib>
 #include <type_traits>
 
 namespace areal {
@@ -633,7 +634,17 @@ hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm
 }
 
 int attn_prefill_tile_rows(int n_q_heads, int n_kv_heads) {
-  return n_q_heads / n_kv_heads <= 8 ? 32 : 16;
+  // tuning knob for sweeps: AREAL_PREFILL_TILE_ROWS=16|32 (read once)
+  static const int forced = [] {
+    const char* e = getenv("AREAL_PREFILL_TILE_ROWS");
+    const int v = e ? atoi(e) : 0;
+    return (v == 16 || v == 32) ? v : 0;
+  }();
+  // at most 3 row-groups per wave keep two work-groups resident per CU at head_dim 128
+  // (7B shape, 7 query heads per KV head: 532 TFLOP/s with 16 positions against 377 with 32)
+  const int G = n_q_heads / n_kv_heads;
+  if (forced && (forced == 16 || G <= 8)) return forced;
+  return G <= 6 ? 32 : 16;
 }
 
 hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work, int n_work,

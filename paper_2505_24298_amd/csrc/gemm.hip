@@ -9,6 +9,7 @@
 #include <algorithm>
 
 #include "kernels.hpp"
+#include <cstdlib>
 
 namespace areal {
 
@@ -478,6 +479,16 @@ int gemm_num_configs() { return 18; }
 // Tile configuration and K split for a product of this shape: rules read off
 // sweeps over every configuration on the MI355X at the decoder's shapes
 // (`cfg` / `splits` >= 0 in launch_gemm_cfg override them).
+// Upper limit of the K split (tuning knob for sweeps: AREAL_GEMM_MAX_SPLITS, read once).
+static int max_splits() {
+  static const int v = [] {
+    const char* e = getenv("AREAL_GEMM_MAX_SPLITS");
+    const int x = e ? atoi(e) : 0;
+    return (x >= 1 && x <= 64) ? x : 8;
+  }();
+  return v;
+}
+
 void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
   const bool dma_ok = (K % BK) == 0;
   const int n_tiles = mode == GEMM_SWIGLU_F16 ? (N + 63) / 64 : (N + 127) / 128;
@@ -508,6 +519,7 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     const int tiles = n_tiles * ((M + bm - 1) / bm);
     sp = (224 + tiles / 2) / std::max(tiles, 1);           // ~one work-group per compute unit
     sp = std::max(1, std::min(sp, std::max(1, nk / 3)));   // at least 3 slabs per split
+    sp = std::min(sp, max_splits());                       // beyond that the atomic adds outweigh the shorter K walk
   }
   *cfg = c;
   *splits = sp;

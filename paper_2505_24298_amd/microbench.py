@@ -10,7 +10,7 @@
       every tile configuration x K split of the projection GEMM at the decoder's
       shapes (qkv, o, gateup, down, lmhead of the 1.5B shape); weights rotate over
       > 1 GB so they come from HBM.
-  python3 paper_2505_24298_amd/microbench.py prefill
+  python3 paper_2505_24298_amd/microbench.py prefill [qwen2-1.5b|qwen2-7b]
       prefill of 32x256, 8x2048, 4x8000 tokens: per-kernel time of one layer.
   python3 paper_2505_24298_amd/microbench.py score
       teacher-forced log-prob pass over 64 trajectories of 512..4096 tokens at the
@@ -113,10 +113,10 @@ def gemm(ms_arg, shapes_arg):
         del Ws, W1s
 
 
-def prefill():
+def prefill(shape_name="qwen2-1.5b"):
     import torch
     from paper_2505_24298_amd import binding, synth
-    cfg = synth.shape("qwen2-1.5b")
+    cfg = synth.shape(shape_name)
     w = _weights(torch, cfg)
     classes = [(binding.K_ATTN_PREFILL, "attn"), (binding.K_GEMM_GATEUP, "gateup"), (binding.K_GEMM_DOWN, "down"),
                (binding.K_GEMM_QKV, "qkv"), (binding.K_GEMM_O, "o")]
@@ -187,7 +187,7 @@ if __name__ == "__main__":
         gemm(sys.argv[2] if len(sys.argv) > 2 else "32,64,128,256",
              sys.argv[3] if len(sys.argv) > 3 else "qkv,o,gateup,down,lmhead")
     elif what == "prefill":
-        prefill()
+        prefill(sys.argv[2] if len(sys.argv) > 2 else "qwen2-1.5b")
     elif what == "score":
         score()
     else:
