@@ -38,26 +38,38 @@ __device__ __forceinline__ const f16* w_row_ptr(const GemmW& W, int tile_n, int 
 }
 
 // Block id -> (row tile, column tile, K split).  Work-groups are handed to the 8
-// XCDs round-robin, so ids equal mod 8 share one L2.  Inside an XCD consecutive
-// work-groups walk super-tiles of up to 8 row tiles x 4 column tiles (column
-// tile = 8*g + xcd): the 32 work-groups resident on an XCD's 32 compute units
-// then share each A slab 4 ways and each W slab 8 ways in that L2.
+// XCDs round-robin, so ids equal mod 8 share one L2.
+//  * Many row tiles (prefill): inside an XCD consecutive work-groups walk
+//    super-tiles of 8 row tiles x 4 column tiles (column tile = 8*g + xcd): the 32
+//    work-groups resident on an XCD's 32 compute units then share each A slab 4
+//    ways and each W slab 8 ways in that L2.
+//  * At most 8 row tiles (decode): a unit = (column tile, K split) with all its
+//    row tiles, so that the work-groups that read one W slab run side by side on
+//    one XCD; units go to the XCDs round-robin, which keeps the XCDs evenly
+//    loaded whatever the number of column tiles (1536 columns = 12 tiles).
 constexpr int SUPER_M = 8, SUPER_N = 4;
-__host__ __device__ __forceinline__ int super_m(int m_tiles) { return m_tiles < SUPER_M ? m_tiles : SUPER_M; }
 __host__ __device__ __forceinline__ int grid_blocks(int m_tiles, int n_tiles, int splits) {
-  const int sm = super_m(m_tiles), n_groups = (n_tiles + 7) / 8;
-  const int mb = (m_tiles + sm - 1) / sm, nb = (n_groups + SUPER_N - 1) / SUPER_N;
-  return 8 * splits * nb * mb * sm * SUPER_N;
+  if (m_tiles <= SUPER_M) return 8 * ((n_tiles * splits + 7) / 8) * m_tiles;
+  const int n_groups = (n_tiles + 7) / 8;
+  const int mb = (m_tiles + SUPER_M - 1) / SUPER_M, nb = (n_groups + SUPER_N - 1) / SUPER_N;
+  return 8 * splits * nb * mb * SUPER_M * SUPER_N;
 }
 __device__ __forceinline__ bool tile_of_block(int id, int m_tiles, int n_tiles, int& tile_m, int& tile_n,
                                               int& split) {
   const int xcd = id & 7, q = id >> 3;
-  const int sm = super_m(m_tiles), n_groups = (n_tiles + 7) >> 3;
-  const int mb = (m_tiles + sm - 1) / sm, nb = (n_groups + SUPER_N - 1) / SUPER_N;
-  const int within = q % (sm * SUPER_N), sq = q / (sm * SUPER_N);
+  if (m_tiles <= SUPER_M) {
+    const int unit = (q / m_tiles) * 8 + xcd;
+    tile_m = q % m_tiles;
+    tile_n = unit % n_tiles;
+    split = unit / n_tiles;   // the up to 7 padding units get split >= the split count: an empty
+    return true;              // K range, on which the kernels return before touching memory
+  }
+  const int n_groups = (n_tiles + 7) >> 3;
+  const int mb = (m_tiles + SUPER_M - 1) / SUPER_M, nb = (n_groups + SUPER_N - 1) / SUPER_N;
+  const int within = q % (SUPER_M * SUPER_N), sq = q / (SUPER_M * SUPER_N);
   const int m_blk = sq % mb, rest = sq / mb;
-  tile_m = m_blk * sm + within % sm;
-  tile_n = ((rest % nb) * SUPER_N + within / sm) * 8 + xcd;
+  tile_m = m_blk * SUPER_M + within % SUPER_M;
+  tile_n = ((rest % nb) * SUPER_N + within / SUPER_M) * 8 + xcd;
   split = rest / nb;
   return tile_m < m_tiles && tile_n < n_tiles;
 }
@@ -484,7 +496,7 @@ static int max_splits() {
   static const int v = [] {
     const char* e = getenv("AREAL_GEMM_MAX_SPLITS");
     const int x = e ? atoi(e) : 0;
-    return (x >= 1 && x <= 64) ? x : 8;
+    return (x >= 1 && x <= 64) ? x : 12;
   }();
   return v;
 }
@@ -508,7 +520,7 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     if (M <= 32) { c = 12; bm = 32; }
     else if (M <= 64) { c = 10; bm = 64; }
     else if (M <= 128) { c = 7; bm = 128; }
-    else { c = 9; bm = 256; }
+    else { c = 8; bm = 128; }          // two 128-row work-groups per CU beat one 256-row tile
   } else {                             // narrow outputs: small row tiles + K split
     if (M <= 64 || K < 4096) { c = 12; bm = 32; }
     else if (M <= 128) { c = 10; bm = 64; }
@@ -516,10 +528,17 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
   }
   int sp = 1;
   if (mode != GEMM_SWIGLU_F16 && M <= 256) {
-    const int tiles = n_tiles * ((M + bm - 1) / bm);
-    sp = (224 + tiles / 2) / std::max(tiles, 1);           // ~one work-group per compute unit
-    sp = std::max(1, std::min(sp, std::max(1, nk / 3)));   // at least 3 slabs per split
-    sp = std::min(sp, max_splits());                       // beyond that the atomic adds outweigh the shorter K walk
+    // Largest split that keeps every XCD at one round of work-groups (32 CUs, one
+    // work-group each): units of (column tile, split) go to the XCDs round-robin, each
+    // with m_tiles work-groups.  Each split keeps at least 3 slabs.  Beyond 8 (12 with a
+    // single row tile) the atomic adds outweigh the shorter K walk.
+    const int m_tiles = (M + bm - 1) / bm;
+    const int cap = std::min(std::max(1, nk / 3), std::min(m_tiles == 1 ? 12 : 8, max_splits()));
+    static const int steps[] = {12, 8, 6, 4, 3, 2, 1};
+    for (int cand : steps) {
+      if (cand > cap) continue;
+      if (((n_tiles * cand + 7) / 8) * m_tiles <= 32 || cand == 1) { sp = cand; break; }
+    }
   }
   *cfg = c;
   *splits = sp;

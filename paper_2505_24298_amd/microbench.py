@@ -87,18 +87,21 @@ def gemm(ms_arg, shapes_arg):
         Ws = [mk() for _ in range(ncopy)]
         W1s = [mk() for _ in range(ncopy)] if mode == 2 else None
         for M in Ms:
-            A = torch.randn((M, K), generator=g, device="cuda").to(torch.float16)
-            C = torch.zeros((M, N), device="cuda", dtype=torch.float16 if mode == 2 else torch.float32)
+            # A and C rotate too: inside a decode step both were last touched by another kernel
+            # (on other XCDs), never by the previous launch of this product
+            As = [torch.randn((M, K), generator=g, device="cuda").to(torch.float16) for _ in range(ncopy)]
+            Cs = [torch.zeros((M, N), device="cuda", dtype=torch.float16 if mode == 2 else torch.float32)
+                  for _ in range(ncopy)]
             for cfg in range(ncfg):
-                for splits in ([1] if mode == 2 or name == "lmhead" else [1, 2, 4, 8, 16]):
+                for splits in ([1] if mode == 2 or name == "lmhead" else [1, 2, 3, 4, 6, 8, 12]):
                     if cfg >= 7 and K % 64:
                         continue
                     iters = 3 * ncopy if wbytes < 1e8 else 6
 
                     def run(n):
                         for i in range(n):
-                            binding.op_gemm(A, Ws[i % ncopy], None if W1s is None else W1s[i % ncopy], C, mode,
-                                            cfg, splits)
+                            binding.op_gemm(As[i % ncopy], Ws[i % ncopy], None if W1s is None else W1s[i % ncopy],
+                                            Cs[i % ncopy], mode, cfg, splits)
                     run(ncopy if wbytes < 1e8 else 2)
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     e0.record()
@@ -110,6 +113,7 @@ def gemm(ms_arg, shapes_arg):
                                           weight_GBps=round(wbytes / us / 1e3, 1),
                                           TFLOPs=round(2.0 * M * N * K * (2 if mode == 2 else 1) / us / 1e6, 1))),
                           flush=True)
+            del As, Cs
         del Ws, W1s
 
 
