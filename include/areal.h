@@ -121,6 +121,14 @@ int areal_load_weights(areal_ctx* ctx, const areal_weights* w, uint64_t version)
  *   tokens     host [cu_seqlens[n_seqs]]  packed prompts, each length >= 1
  *   cu_seqlens host [n_seqs+1] prefix sums of the prompt lengths, [0] = 0
  *   logits_out device float32 [n_seqs, vocab]
+ * Sequences of one call whose prompts are identical (the paper samples 16
+ * answers per prompt, Table 3) share the KV blocks of the prompt: the first of
+ * them computes the prompt, each of the others holds the same full blocks (all
+ * but the block with the prompt's last token) and computes only the positions
+ * after them.  Nothing else changes for the caller: every sequence has its own
+ * id, logits row, history and later blocks, and a shared block returns to the
+ * pool when its last holder terminates.  areal_update_weights_interrupt
+ * recomputes a shared part once.
  * n_seqs == 0 is a no-op (AREAL_OK, no pointer is read).  On any error no
  * sequence is admitted and no block is reserved. */
 int areal_prefill(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
@@ -172,7 +180,8 @@ int areal_sample_logprob(areal_ctx* ctx, int32_t n, const float* logits,
  *   live_seq_ids_out  host int32 [max_seqs]  their ids, ascending
  *   logits_out        device float32 [n_live, vocab] in that order; may be
  *                     NULL only if no sequence is live
- *   reprefilled_tokens_out  host int64 or NULL: prefix tokens recomputed */
+ *   reprefilled_tokens_out  host int64 or NULL: positions recomputed (shared
+ *                     prompt blocks count once) */
 int areal_update_weights_interrupt(areal_ctx* ctx, const areal_weights* new_w,
                                    uint64_t new_version, int32_t* n_live_out,
                                    int32_t* live_seq_ids_out, float* logits_out,

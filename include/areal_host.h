@@ -25,8 +25,13 @@ void areal_kvalloc_destroy(areal_kvalloc* a);
 /* Grow sequence `seq` so that it can hold n_tokens.  0 on success; AREAL_E_NOMEM
  * (and no change) if the pool or the per-sequence limit is too small. */
 int areal_kvalloc_reserve(areal_kvalloc* a, int32_t seq, int64_t n_tokens);
-/* Return all blocks of `seq` to the pool. */
+/* Drop `seq`'s hold on all its blocks; a block returns to the pool when its
+ * last holder lets go. */
 void areal_kvalloc_release(areal_kvalloc* a, int32_t seq);
+/* Prompt-prefix sharing (the paper samples 16 answers per prompt, Table 3):
+ * `dst`, which must hold no blocks, starts out holding the first n_blocks blocks
+ * of `src` as well.  0 on success, AREAL_E_INVAL otherwise (no change). */
+int areal_kvalloc_share(areal_kvalloc* a, int32_t dst, int32_t src, int32_t n_blocks);
 int64_t areal_kvalloc_free_blocks(const areal_kvalloc* a);
 /* Copy up to `cap` block ids of `seq` into out (host); returns the block count. */
 int32_t areal_kvalloc_table(const areal_kvalloc* a, int32_t seq, int32_t* out, int32_t cap);

@@ -91,6 +91,7 @@ _SIGNATURES = {
     "areal_kvalloc_destroy": (None, [C.c_void_p]),
     "areal_kvalloc_reserve": (C.c_int, [C.c_void_p, C.c_int32, C.c_int64]),
     "areal_kvalloc_release": (None, [C.c_void_p, C.c_int32]),
+    "areal_kvalloc_share": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
     "areal_kvalloc_free_blocks": (C.c_int64, [C.c_void_p]),
     "areal_kvalloc_table": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, C.c_int32]),
     "areal_kvalloc_shuffle": (None, [C.c_void_p, C.c_uint64]),

@@ -157,6 +157,31 @@ hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta r
   return hipGetLastError();
 }
 
+// Prompt-prefix sharing: block-table entries of sequences that start out holding
+// another sequence's blocks ({slot, index, block} triples), and the copy of the
+// shared part of the token history ({dst slot, src slot, n tokens} triples).
+__global__ __launch_bounds__(256) void table_patch_kernel(const int32_t* __restrict__ patch, int n,
+                                                          SeqState st) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) st.table[(int64_t)patch[3 * i] * st.max_blocks + patch[3 * i + 1]] = patch[3 * i + 2];
+}
+__global__ __launch_bounds__(256) void hist_copy_kernel(const int32_t* __restrict__ job, SeqState st) {
+  const int dst = job[3 * blockIdx.x], src = job[3 * blockIdx.x + 1], n = job[3 * blockIdx.x + 2];
+  const int32_t* s = st.hist + (int64_t)src * st.max_seq_len;
+  int32_t* d = st.hist + (int64_t)dst * st.max_seq_len;
+  for (int t = threadIdx.x; t < n; t += 256) d[t] = s[t];
+}
+hipError_t launch_table_patch(hipStream_t s, const int32_t* patch, int n, SeqState st) {
+  if (n <= 0 || !patch) return hipErrorInvalidValue;
+  table_patch_kernel<<<(n + 255) / 256, 256, 0, s>>>(patch, n, st);
+  return hipGetLastError();
+}
+hipError_t launch_hist_copy(hipStream_t s, const int32_t* jobs, int n, SeqState st) {
+  if (n <= 0 || !jobs) return hipErrorInvalidValue;
+  hist_copy_kernel<<<n, 256, 0, s>>>(jobs, st);
+  return hipGetLastError();
+}
+
 // Per-pass metadata travels from the pinned host ring to its device mirror in a
 // kernel of the library's own (16-byte words; src is device-mapped host memory).
 __global__ __launch_bounds__(256) void stage_copy_kernel(const u32x4* __restrict__ src,

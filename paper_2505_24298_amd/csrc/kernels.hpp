@@ -29,6 +29,9 @@ hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta r
                                const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                                const float* sin_tab, f16* q_out, f16* arena_layer, KvGeom geom,
                                int n_q_heads);
+// {slot, block index, block id} triples -> block table; {dst slot, src slot, n tokens} -> history
+hipError_t launch_table_patch(hipStream_t s, const int32_t* patch, int n, SeqState st);
+hipError_t launch_hist_copy(hipStream_t s, const int32_t* jobs, int n, SeqState st);
 hipError_t launch_stage_copy(hipStream_t s, const void* src_host_mapped, void* dst, size_t bytes);
 hipError_t launch_to_f16(hipStream_t s, const void* src, int src_is_bf16, f16* dst, int64_t n);
 

@@ -14,7 +14,7 @@ class KvAllocator {
  public:
   KvAllocator(int64_t n_blocks, int max_seqs, int max_blocks_per_seq, int block_tokens)
       : n_blocks_(n_blocks), max_blocks_per_seq_(max_blocks_per_seq), block_tokens_(block_tokens),
-        seq_blocks_(max_seqs) {
+        seq_blocks_(max_seqs), refcnt_(n_blocks, 0) {
     free_.reserve(n_blocks);
     for (int64_t b = n_blocks - 1; b >= 0; --b) free_.push_back((int32_t)b);   // pop() yields 0,1,2..
   }
@@ -35,13 +35,28 @@ class KvAllocator {
     if (extra < 0 || extra > n_free()) return false;
     for (int64_t i = 0; i < extra; ++i) {
       seq_blocks_[seq].push_back(free_.back());
+      refcnt_[free_.back()] = 1;
       free_.pop_back();
     }
     return true;
   }
+  // Sequence `dst` (which must hold no blocks) starts out with the first n blocks of
+  // `src`, shared: a block returns to the pool when its last holder releases it.
+  bool share_prefix(int dst, int src, int n) {
+    if (dst == src || !seq_blocks_[dst].empty() || n < 0 || n > (int)seq_blocks_[src].size() ||
+        n > max_blocks_per_seq_)
+      return false;
+    for (int i = 0; i < n; ++i) {
+      seq_blocks_[dst].push_back(seq_blocks_[src][i]);
+      ++refcnt_[seq_blocks_[src][i]];
+    }
+    return true;
+  }
+  int refcount(int32_t block) const { return refcnt_[block]; }
   void release(int seq) {
     auto& v = seq_blocks_[seq];
-    for (auto it = v.rbegin(); it != v.rend(); ++it) free_.push_back(*it);
+    for (auto it = v.rbegin(); it != v.rend(); ++it)
+      if (--refcnt_[*it] == 0) free_.push_back(*it);
     v.clear();
   }
   // Test hook: deterministic shuffle of the free list (placement must not matter).
@@ -58,6 +73,7 @@ class KvAllocator {
   int max_blocks_per_seq_, block_tokens_;
   std::vector<int32_t> free_;
   std::vector<std::vector<int32_t>> seq_blocks_;
+  std::vector<int32_t> refcnt_;          // holders per block
 };
 
 // A span of one sequence to run through the decoder: positions [pos0, pos0+len).

@@ -13,6 +13,9 @@
 #include "../../include/areal_host.h"
 #include "../../include/areal_ops.h"
 #include "kernels.hpp"
+#include <unordered_map>
+#include <unordered_set>
+
 #include "kv_alloc.hpp"
 #include "gate.hpp"
 
@@ -93,6 +96,7 @@ Layout make_layout(const areal_model_cfg& c) {
 struct SeqInfo {
   bool live = false;
   int32_t len = 0;
+  int32_t n_shared = 0;                 // leading KV blocks held together with other sequences
   int64_t pending_version = 0;          // version whose logits the next token is sampled from
   std::vector<int64_t> versions;        // per position; -1 = prompt
 };
@@ -485,6 +489,26 @@ int run_spans(areal_ctx* c, const std::vector<Span>& spans, const int32_t* token
   return AREAL_OK;
 }
 
+// Send `n` int32 triples through the metadata ring (in as many segments as it takes) and run
+// `launch` on each staged chunk.
+template <class F>
+int stage_triples(areal_ctx* c, const std::vector<int32_t>& tri, F launch) {
+  const size_t n = tri.size() / 3;
+  const size_t per_seg = (size_t)(c->seg_bytes / 64) * 64 / 12;
+  for (size_t i = 0; i < n; i += per_seg) {
+    const size_t k = std::min(per_seg, n - i);
+    int rc = ring_begin(c, align_up(k * 12, 64));
+    if (rc) return rc;
+    const uint64_t start = c->seg_used;
+    Staged st = ring_take(c, k * 12);
+    memcpy(st.host, tri.data() + 3 * i, k * 12);
+    rc = ring_flush(c, start);
+    if (rc) return rc;
+    HIP_TRY(c, launch((const int32_t*)st.dev, (int)k));
+  }
+  return AREAL_OK;
+}
+
 }  // namespace
 
 // ============================================================== C boundary ===
@@ -608,6 +632,28 @@ int areal_prefill(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t
   if (n > g.max_seqs) return fail(c, AREAL_E_INVAL, "more sequences than max_seqs");
   if (cu[0] != 0) return fail(c, AREAL_E_INVAL, "cu_seqlens[0] must be 0");
   std::vector<char> seen(g.max_seqs, 0);
+  // Prompt-prefix sharing (16 answers are sampled per prompt): a sequence whose prompt equals
+  // that of an earlier sequence of this call holds that sequence's full prompt blocks too and
+  // computes only what follows them.  One block fewer is shared when the prompt ends on a
+  // block boundary, so that every sequence has a last row of its own to produce logits from.
+  std::vector<int> leader(n, -1), n_sh(n, 0);
+  {
+    std::unordered_map<uint64_t, std::vector<int>> by_hash;
+    for (int i = 0; i < n; ++i) {
+      const int64_t len = (int64_t)cu[i + 1] - cu[i];
+      if (len < 1) continue;                       // reported below
+      uint64_t h = 1469598103934665603ull ^ (uint64_t)len;
+      for (int64_t t = cu[i]; t < cu[i + 1]; ++t) h = (h ^ (uint32_t)tokens[t]) * 1099511628211ull;
+      auto& bucket = by_hash[h];
+      for (int j : bucket)
+        if (cu[j + 1] - cu[j] == len && !memcmp(tokens + cu[j], tokens + cu[i], (size_t)len * 4)) {
+          leader[i] = j;
+          n_sh[i] = (int)((len - 1) / AREAL_KV_BLOCK_TOKENS);
+          break;
+        }
+      if (leader[i] < 0) bucket.push_back(i);
+    }
+  }
   int64_t need_blocks = 0;
   for (int i = 0; i < n; ++i) {
     const int id = seq_ids[i];
@@ -617,26 +663,47 @@ int areal_prefill(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t
     const int64_t len = (int64_t)cu[i + 1] - cu[i];
     if (len < 1) return fail(c, AREAL_E_INVAL, "every prompt needs at least one token");
     if (len > g.max_seq_len) return fail(c, AREAL_E_NOMEM, "prompt longer than max_seq_len");
-    need_blocks += c->alloc->blocks_for(len);
+    need_blocks += c->alloc->blocks_for(len) - n_sh[i];
   }
   for (int64_t t = 0; t < cu[n]; ++t)
     if (tokens[t] < 0 || tokens[t] >= g.vocab) return fail(c, AREAL_E_INVAL, "token id outside the vocabulary");
   if (need_blocks > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
   std::vector<Span> spans;
   std::vector<int64_t> tok_off;
+  std::vector<int32_t> patches, hist_jobs;
   for (int i = 0; i < n; ++i) {
     const int id = seq_ids[i], len = cu[i + 1] - cu[i];
+    const int shared_len = n_sh[i] * AREAL_KV_BLOCK_TOKENS;
+    if (n_sh[i] > 0) {
+      const int lead_id = seq_ids[leader[i]];
+      c->alloc->share_prefix(id, lead_id, n_sh[i]);
+      c->seqs[lead_id].n_shared = n_sh[i];
+      const auto& lb = c->alloc->blocks(lead_id);
+      for (int b = 0; b < n_sh[i]; ++b) { patches.push_back(id); patches.push_back(b); patches.push_back(lb[b]); }
+      hist_jobs.push_back(id); hist_jobs.push_back(lead_id); hist_jobs.push_back(shared_len);
+    }
     c->alloc->reserve(id, len);
     SeqInfo& s = c->seqs[id];
     s.live = true;
     s.len = len;
+    s.n_shared = std::max(s.n_shared, n_sh[i]);
     s.pending_version = c->version;
     s.versions.assign(len, -1);
-    spans.push_back(Span{id, 0, len, i});
-    tok_off.push_back(cu[i]);
+    spans.push_back(Span{id, shared_len, len - shared_len, i});
+    tok_off.push_back(cu[i] + shared_len);
   }
-  return run_spans(c, spans, tokens, tok_off, true, logits_out);
+  SeqState st = c->seq_state();
+  if (!patches.empty()) {
+    int rc = stage_triples(c, patches, [&](const int32_t* d, int k) { return launch_table_patch(c->stream, d, k, st); });
+    if (rc) return rc;
+  }
+  int rc = run_spans(c, spans, tokens, tok_off, true, logits_out);
+  if (rc) return rc;
+  if (!hist_jobs.empty())       // the shared part of the token history, once the leaders' rows have run
+    rc = stage_triples(c, hist_jobs, [&](const int32_t* d, int k) { return launch_hist_copy(c->stream, d, k, st); });
+  return rc;
 }
+
 
 int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t* tokens_in,
                       float* logits_out) {
@@ -750,10 +817,16 @@ int areal_update_weights_interrupt(areal_ctx* c, const areal_weights* new_w, uin
   std::vector<Span> spans;
   int64_t total = 0;
   int nl = 0;
+  // a shared prompt prefix is recomputed once, by the first live sequence that holds it
+  std::unordered_set<int32_t> claimed;
   for (int id = 0; id < c->cfg.max_seqs; ++id)
     if (c->seqs[id].live) {
-      spans.push_back(Span{id, 0, c->seqs[id].len, nl});
-      total += c->seqs[id].len;
+      const SeqInfo& q = c->seqs[id];
+      int pos0 = 0;
+      if (q.n_shared > 0 && !claimed.insert(c->alloc->blocks(id)[0]).second)
+        pos0 = q.n_shared * AREAL_KV_BLOCK_TOKENS;
+      spans.push_back(Span{id, pos0, q.len - pos0, nl});
+      total += q.len - pos0;
       ++nl;
     }
   if (nl > 0 && !logits_out) return fail(c, AREAL_E_INVAL, "logits_out is NULL with live sequences");
@@ -936,6 +1009,9 @@ areal_kvalloc* areal_kvalloc_create(int64_t n_blocks, int32_t max_seqs, int32_t 
 void areal_kvalloc_destroy(areal_kvalloc* a) { delete a; }
 int areal_kvalloc_reserve(areal_kvalloc* a, int32_t seq, int64_t n_tokens) { return a->a.reserve(seq, n_tokens) ? 0 : AREAL_E_NOMEM; }
 void areal_kvalloc_release(areal_kvalloc* a, int32_t seq) { a->a.release(seq); }
+int areal_kvalloc_share(areal_kvalloc* a, int32_t dst, int32_t src, int32_t n_blocks) {
+  return a->a.share_prefix(dst, src, n_blocks) ? 0 : AREAL_E_INVAL;
+}
 int64_t areal_kvalloc_free_blocks(const areal_kvalloc* a) { return a->a.n_free(); }
 int32_t areal_kvalloc_table(const areal_kvalloc* a, int32_t seq, int32_t* out, int32_t cap) {
   const auto& b = a->a.blocks(seq);

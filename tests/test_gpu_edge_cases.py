@@ -235,3 +235,52 @@ def test_weight_update_with_nothing_in_flight(torch, binding):
     eng.decode_step([0, 1], toks)
     assert eng.get_versions(0)[-1] == 7
     eng.close()
+
+
+def test_shared_prompt_prefix_with_interrupt_and_early_termination(torch, binding):
+    """Four samples of each of two prompts (lengths 37 and 48: the second ends on
+    a block boundary) admitted in one call: the samples share the prompt's full
+    KV blocks.  The first sample of a prompt (whose rows computed the shared
+    blocks) terminates early; a weight update then recomputes every live prefix,
+    the shared part once; decoding goes on.  Logits against the oracle throughout."""
+    from oracle import rollout
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 31)
+    w2 = synth.perturb_weights(w, 1002, scale=5e-3, round_bf16=False)
+    rng = np.random.default_rng(12)
+    base = [rng.integers(0, cfg["vocab"], size=n).astype(np.int32) for n in (37, 48)]
+    prompts = [base[0]] * 4 + [base[1]] * 4
+    ids = list(range(8))
+    eng = _engine(binding, cfg, w, kv_blocks=40)
+    wk = _oracle(cfg, w)
+    for s, p in zip(ids, prompts):
+        wk.add(s, p)
+    logits = eng.prefill(ids, prompts)
+    # 37 tokens: 3 blocks, 2 shared; 48 tokens: 3 blocks, 2 shared (one fewer than full)
+    total, free = eng.kv_blocks()
+    assert total - free == (3 + 3 * 1) + (3 + 3 * 1)
+    for s in ids:
+        assert eng.get_tokens(s).tolist() == prompts[s].tolist()
+    live = list(ids)
+    for step in range(20):
+        toks = _check_step(torch, eng, wk, live, logits)
+        if step == 3:                                  # the samples that computed the shared blocks leave
+            for s in (0, 4):
+                eng.free_seq(s)
+                wk.finish(s)
+            keep = [i for i, s in enumerate(live) if s not in (0, 4)]
+            toks = toks[torch.tensor(keep, device=toks.device)].contiguous()
+            live = [s for s in live if s not in (0, 4)]
+        logits = eng.decode_step(live, toks)
+        if step == 9:
+            wk.update_weights(_f16_weights(w2), 1)
+            got_live, logits, retok = eng.update_weights_interrupt(binding.weights_to_device(w2, bf16=False), 1)
+            assert got_live.tolist() == live
+            # each prompt's 32 shared positions are recomputed once, not three times
+            assert retok == sum(len(wk.tokens[s]) for s in live) - 2 * 2 * 32
+    for s in live:
+        assert eng.get_tokens(s).tolist() == wk.tokens[s][:-1] or eng.get_tokens(s).tolist() == wk.tokens[s]
+    for s in live:
+        eng.free_seq(s)
+    assert eng.kv_blocks() == (40, 40)
+    eng.close()

@@ -199,3 +199,24 @@ def _budget(o):
     c = staleness.StalenessGate(o.B, o.eta, o.version)
     c.submitted = o.submitted
     return c.submit(10 ** 6)
+
+
+def test_kvalloc_shared_prefix_refcounts():
+    L = binding.lib()
+    a = L.areal_kvalloc_create(10, 4, 8)
+    assert L.areal_kvalloc_reserve(a, 0, 40) == 0 and _table(L, a, 0) == [0, 1, 2]
+    assert L.areal_kvalloc_share(a, 1, 0, 2) == 0 and _table(L, a, 1) == [0, 1]
+    assert L.areal_kvalloc_share(a, 2, 0, 2) == 0
+    assert L.areal_kvalloc_share(a, 1, 0, 1) == binding.E_INVAL          # holder is not empty
+    assert L.areal_kvalloc_share(a, 3, 0, 4) == binding.E_INVAL          # more than the source holds
+    assert L.areal_kvalloc_reserve(a, 1, 40) == 0 and _table(L, a, 1) == [0, 1, 3]   # own third block
+    assert L.areal_kvalloc_free_blocks(a) == 6
+    L.areal_kvalloc_release(a, 0)                                        # the first holder leaves:
+    assert L.areal_kvalloc_free_blocks(a) == 7                           # only its own block 2 returns
+    L.areal_kvalloc_release(a, 1)
+    assert L.areal_kvalloc_free_blocks(a) == 8                           # block 3; 0 and 1 still held by 2
+    L.areal_kvalloc_release(a, 2)
+    assert L.areal_kvalloc_free_blocks(a) == 10
+    assert L.areal_kvalloc_reserve(a, 3, 160) == binding.E_NOMEM         # per-sequence limit 8 blocks
+    assert L.areal_kvalloc_reserve(a, 3, 128) == 0 and len(set(_table(L, a, 3))) == 8
+    L.areal_kvalloc_destroy(a)
