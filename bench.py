@@ -105,6 +105,25 @@ def prefill_work(cfg, prompts):
     return rows, float(2 * p_layers * rows + 2 * V * H * len(prompts) + 4 * qd * L * pairs)
 
 
+def reprefill_flops(cfg, prompts, lens, retok):
+    """Flops of one re-prefill over live sequences of the given current lengths:
+    a prompt's shared blocks are recomputed by the first live sequence holding
+    them only (retok = positions the library reports as recomputed)."""
+    H, F, V, L = cfg["hidden"], cfg["ffn"], cfg["vocab"], cfg["n_layers"]
+    qd, kd = cfg["n_q_heads"] * cfg["head_dim"], cfg["n_kv_heads"] * cfg["head_dim"]
+    p_layers = L * (qd * H + 2 * kd * H + H * qd + 3 * F * H)
+    seen, pairs, rows = set(), 0.0, 0
+    for p, n in zip(prompts, lens):
+        key = np.asarray(p, dtype=np.int32).tobytes()
+        start = ((len(p) - 1) // 16) * 16 if key in seen else 0
+        seen.add(key)
+        n = int(n)
+        rows += n - start
+        pairs += n * (n + 1) / 2 - start * (start + 1) / 2
+    assert rows == retok, (rows, retok)
+    return float(2 * p_layers * rows + 2 * V * H * len(prompts) + 4 * qd * L * pairs)
+
+
 def rollout(eng, torch, cfg, prompts, out_lens, temperature, top_p, seed, interrupt_every=0,
             weight_sets=None, profile=None):
     """Run one whole rollout.  Sequences are ordered by output length
@@ -164,6 +183,8 @@ def rollout(eng, torch, cfg, prompts, out_lens, temperature, top_p, seed, interr
             _, _, retok = eng.update_weights_interrupt(weight_sets[version % len(weight_sets)], version,
                                                        logits_out=logits_b)
             b.record()
+            res["reprefill_flops"] = res.get("reprefill_flops", 0.0) + reprefill_flops(
+                cfg, prompts[:live], plen[:live] + gen, retok)
             re_events.append((a, b))
             logits, logits_b = logits_b, logits
             res["reprefill_tokens"] += retok
@@ -504,6 +525,8 @@ def main():
     if args.interrupt_every:
         rt, rms = sum(r["reprefill_tokens"] for r in runs), sum(r["reprefill_ms"] for r in runs)
         out["interrupt"] = {"count": runs[0]["interrupts"], "reprefill_tokens_per_s": round(rt / (rms * 1e-3), 1),
+                            "reprefill_mfma_frac_of_peak": round(sum(r["reprefill_flops"] for r in runs) / (rms * 1e-3)
+                                                                 / (MFMA_F16_PEAK_TFLOPS * 1e12), 4),
                             "reprefill_ms_total": round(rms, 1),
                             "reprefill_over_decode_time": round(rms / dec_ms, 4)}
     eng.close()
