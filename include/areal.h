@@ -208,6 +208,20 @@ int areal_recompute_logprob(areal_ctx* ctx, int32_t n_seqs, const int32_t* token
                             const int32_t* cu_seqlens, float temperature,
                             float* logits_scratch, int32_t scratch_rows, float* logp_out);
 
+/* Section 5.2, Eq. 5 (decoupled PPO objective), forward value over n tokens:
+ *   u_t = exp(logp_theta - logp_prox),  w_t = exp(logp_prox - logp_behav),
+ *   obj_t = w_t * min(u_t A_t, clip(u_t, 1 - eps, 1 + eps) A_t)      (0 where mask is 0)
+ * logp_behav is what areal_sample_logprob emitted, logp_prox what
+ * areal_recompute_logprob returns for the proximal parameters, logp_theta the
+ * same for the current ones.  All arrays device, float32 [n]; mask device
+ * uint8 [n] or NULL; obj_out device float32 [n] or NULL.
+ *   sums_out  device float64 [3], ACCUMULATED into (the caller clears it):
+ *             sum of obj_t, tokens whose clipped term is the smaller one,
+ *             tokens counted. */
+int areal_ppo_objective(areal_ctx* ctx, int64_t n, const float* logp_theta, const float* logp_prox,
+                        const float* logp_behav, const float* adv, const uint8_t* mask, float eps,
+                        float* obj_out, double* sums_out);
+
 /* Termination (Section 4.1 "until the next interruption or termination"): the
  * caller decides when a sequence ends; its KV blocks return to the pool. */
 int areal_free_seq(areal_ctx* ctx, int32_t seq_id);

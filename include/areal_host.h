@@ -62,6 +62,17 @@ int64_t areal_gate_budget(const areal_gate* g);      /* requests admissible righ
 int areal_gate_set_version(areal_gate* g, int64_t version);
 int64_t areal_gate_submitted(const areal_gate* g);   /* N_r */
 
+/* Appendix, Algorithm 1 (dynamic batching): partition n sequences of the given
+ * lengths into micro-batches of total length <= capacity, at least k_min of
+ * them, balanced in sequence count: longest first, a sequence opens a new
+ * micro-batch while fewer than k_min exist or none has room, else joins the
+ * micro-batch with room that holds the fewest sequences (earliest on a tie).
+ * batch_of (host [n]) receives each sequence's micro-batch index; returns the
+ * number of micro-batches, or AREAL_E_INVAL for n < 0, lengths < 1,
+ * capacity < 1 or k_min < 1.  A sequence longer than capacity stands alone. */
+int32_t areal_dynamic_batching(int32_t n, const int32_t* lens, int64_t capacity, int32_t k_min,
+                               int32_t* batch_of);
+
 #ifdef __cplusplus
 }
 #endif

@@ -72,6 +72,9 @@ _SIGNATURES = {
     "areal_gate_budget": (C.c_int64, [C.c_void_p]),
     "areal_gate_set_version": (C.c_int, [C.c_void_p, C.c_int64]),
     "areal_gate_submitted": (C.c_int64, [C.c_void_p]),
+    "areal_dynamic_batching": (C.c_int32, [C.c_int32, _I32P, C.c_int64, C.c_int32, _I32P]),
+    "areal_ppo_objective": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_float, C.c_void_p, C.c_void_p]),
     "areal_recompute_logprob": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_float, C.c_void_p,
                                           C.c_int32, C.c_void_p]),
     "areal_free_seq": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -228,6 +231,24 @@ class Areal:
         self._weights_keepalive = self._weights_keepalive[-1:] + [keep]
         n = n_live.value
         return ids[:n].copy(), logits_out[:n], retok.value
+
+    def ppo_objective(self, logp_theta, logp_prox, logp_behav, adv, eps, mask=None, per_token=False):
+        """Decoupled PPO objective over device float32 arrays: returns (sum, clipped tokens,
+        counted tokens) as a host tuple and, with per_token, the per-token objective tensor."""
+        torch = self.torch
+        n = logp_theta.numel()
+        for t in (logp_theta, logp_prox, logp_behav, adv):
+            assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == n
+        sums = torch.zeros(3, dtype=torch.float64, device=self.device)
+        obj = torch.empty(n, dtype=torch.float32, device=self.device) if per_token else None
+        if mask is not None:
+            assert mask.is_cuda and mask.dtype == torch.uint8 and mask.numel() == n
+        self._check(self.L.areal_ppo_objective(self.ctx, n, logp_theta.data_ptr(), logp_prox.data_ptr(),
+                                               logp_behav.data_ptr(), adv.data_ptr(),
+                                               None if mask is None else mask.data_ptr(), float(eps),
+                                               None if obj is None else obj.data_ptr(), sums.data_ptr()))
+        s = sums.cpu().numpy()
+        return (float(s[0]), int(s[1]), int(s[2])), obj
 
     def recompute_logprob(self, seqs, temperature=1.0, scratch_rows=256, scratch=None):
         """Log-prob of every token of every sequence given the tokens before it

@@ -9,6 +9,7 @@
 #pragma once
 #include <stdint.h>
 #include <algorithm>
+#include <vector>
 
 namespace areal {
 
@@ -41,5 +42,33 @@ class StalenessGate {
   int64_t B_, eta_;
   int64_t version_ = 0, submitted_ = 0;
 };
+
+// Dynamic batching: sequences longest first; a sequence opens a new micro-batch while
+// fewer than k_min exist or when none has room (total length <= capacity), otherwise it
+// joins, among those with room, the one holding the fewest sequences (first created on a
+// tie).  Equal lengths keep their input order.  batch_of[i] = micro-batch of sequence i;
+// returns the number of micro-batches.
+inline int dynamic_batching(const int32_t* lens, int n, int64_t capacity, int k_min, int32_t* batch_of) {
+  std::vector<int> order(n);
+  for (int i = 0; i < n; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return lens[a] > lens[b]; });
+  std::vector<int64_t> total;
+  std::vector<int> count;
+  for (int i : order) {
+    int best = -1;
+    if ((int)total.size() >= k_min)
+      for (int b = 0; b < (int)total.size(); ++b)
+        if (total[b] + lens[i] <= capacity && (best < 0 || count[b] < count[best])) best = b;
+    if (best < 0) {
+      best = (int)total.size();
+      total.push_back(0);
+      count.push_back(0);
+    }
+    total[best] += lens[i];
+    ++count[best];
+    batch_of[i] = best;
+  }
+  return (int)total.size();
+}
 
 }  // namespace areal

@@ -88,4 +88,10 @@ hipError_t launch_sampler(hipStream_t s, int n, int vocab, const float* logits, 
 hipError_t launch_token_logprob(hipStream_t s, const float* logits, int n, int vocab, float inv_t,
                                 const int32_t* target, const int32_t* pos, float* out);
 
+// Decoupled PPO objective (forward): sums[0..2] += {sum of per-token objective, tokens whose
+// clipped term is active, tokens counted}; obj_out (optional) per token; mask (optional) bytes.
+hipError_t launch_ppo_objective(hipStream_t s, int n, const float* logp_theta, const float* logp_prox,
+                                const float* logp_behav, const float* adv, const uint8_t* mask, float eps,
+                                float* obj_out, double* sums);
+
 }  // namespace areal

@@ -893,6 +893,19 @@ int areal_recompute_logprob(areal_ctx* c, int32_t n, const int32_t* tokens, cons
   return AREAL_OK;
 }
 
+int areal_ppo_objective(areal_ctx* c, int64_t n, const float* logp_theta, const float* logp_prox,
+                        const float* logp_behav, const float* adv, const uint8_t* mask, float eps,
+                        float* obj_out, double* sums_out) {
+  if (!c) return AREAL_E_INVAL;
+  if (n == 0) return AREAL_OK;
+  if (n < 0 || n > INT32_MAX || !logp_theta || !logp_prox || !logp_behav || !adv || !sums_out ||
+      !(eps >= 0.f))
+    return fail(c, AREAL_E_INVAL, "NULL argument, bad count or negative clip range");
+  HIP_TRY(c, launch_ppo_objective(c->stream, (int)n, logp_theta, logp_prox, logp_behav, adv, mask, eps, obj_out,
+                                  sums_out));
+  return AREAL_OK;
+}
+
 int areal_free_seq(areal_ctx* c, int32_t id) {
   if (!c) return AREAL_E_INVAL;
   if (id < 0 || id >= c->cfg.max_seqs || !c->seqs[id].live) return fail(c, AREAL_E_INVAL, "sequence not live");
@@ -1033,6 +1046,14 @@ int areal_gate_set_version(areal_gate* g, int64_t version) {
   return g->g.set_version(version) ? AREAL_OK : AREAL_E_STATE;
 }
 int64_t areal_gate_submitted(const areal_gate* g) { return g ? g->g.submitted() : 0; }
+
+int32_t areal_dynamic_batching(int32_t n, const int32_t* lens, int64_t capacity, int32_t k_min,
+                               int32_t* batch_of) {
+  if (n < 0 || capacity < 1 || k_min < 1 || (n > 0 && (!lens || !batch_of))) return AREAL_E_INVAL;
+  for (int i = 0; i < n; ++i)
+    if (lens[i] < 1) return AREAL_E_INVAL;
+  return dynamic_batching(lens, n, capacity, k_min, batch_of);
+}
 
 int32_t areal_plan_passes(int32_t n_spans, const int32_t* lens, int32_t max_rows, int32_t* out, int32_t cap) {
   std::vector<Span> spans;

@@ -3,6 +3,8 @@
 // One work-group per row, one pass over the row: every thread keeps a running
 // (max, sum of exponentials) pair over its elements, the pairs are combined
 // across the wave with shuffles and across waves through LDS.
+#include <algorithm>
+
 #include "kernels.hpp"
 
 namespace areal {
@@ -50,7 +52,52 @@ __global__ __launch_bounds__(LP_THREADS) void token_logprob_kernel(
   }
 }
 
+// Decoupled PPO objective, forward value: per token
+//   u = exp(lt - lp), w = exp(lp - lb), obj = w * min(u A, clip(u, 1-eps, 1+eps) A),
+// optional mask; sums[0] += sum obj, sums[1] += number of tokens whose clipped term is the
+// smaller one, sums[2] += tokens counted.  Float64 accumulation (one atomic per work-group).
+__global__ __launch_bounds__(256) void ppo_objective_kernel(
+    int n, const float* __restrict__ lt, const float* __restrict__ lp, const float* __restrict__ lb,
+    const float* __restrict__ adv, const uint8_t* __restrict__ mask, float eps,
+    float* __restrict__ obj_out, double* __restrict__ sums) {
+  __shared__ double part[3][4];
+  double s_obj = 0.0, s_clip = 0.0, s_cnt = 0.0;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) {
+    const bool on = !mask || mask[i];
+    const float u = expf(lt[i] - lp[i]), w = expf(lp[i] - lb[i]), a = adv[i];
+    const float unclipped = u * a, clipped = fminf(fmaxf(u, 1.f - eps), 1.f + eps) * a;
+    const float o = on ? w * fminf(unclipped, clipped) : 0.f;
+    if (obj_out) obj_out[i] = o;
+    s_obj += (double)o;
+    s_clip += (on && clipped < unclipped) ? 1.0 : 0.0;
+    s_cnt += on ? 1.0 : 0.0;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    s_obj += __shfl_xor(s_obj, o);
+    s_clip += __shfl_xor(s_clip, o);
+    s_cnt += __shfl_xor(s_cnt, o);
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) { part[0][wave] = s_obj; part[1][wave] = s_clip; part[2][wave] = s_cnt; }
+  __syncthreads();
+  if (threadIdx.x < 3) {
+    const double v = part[threadIdx.x][0] + part[threadIdx.x][1] + part[threadIdx.x][2] + part[threadIdx.x][3];
+    atomicAdd(&sums[threadIdx.x], v);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_ppo_objective(hipStream_t s, int n, const float* lt, const float* lp, const float* lb,
+                                const float* adv, const uint8_t* mask, float eps, float* obj_out,
+                                double* sums) {
+  if (n < 0 || !lt || !lp || !lb || !adv || !sums) return hipErrorInvalidValue;
+  if (n == 0) return hipSuccess;
+  const int grid = std::min((n + 255) / 256, 1024);
+  ppo_objective_kernel<<<grid, 256, 0, s>>>(n, lt, lp, lb, adv, mask, eps, obj_out, sums);
+  return hipGetLastError();
+}
 
 hipError_t launch_token_logprob(hipStream_t s, const float* logits, int n, int vocab, float inv_t,
                                 const int32_t* target, const int32_t* pos, float* out) {

@@ -132,3 +132,28 @@ def test_scoring_errors(torch, binding):
     assert e.value.code == binding.E_NOMEM
     assert eng.seq_len(0) == 20 and eng.kv_blocks() == (2, 0)
     eng.close()
+
+
+def test_ppo_objective_matches_oracle(torch, binding):
+    """Decoupled PPO objective (Eq. 5) over 100,003 tokens (several work-groups,
+    a ragged tail), with and without a mask, against the float64 oracle."""
+    from oracle import trainer_side
+    cfg = synth.shape("tiny")
+    eng = _engine(binding, cfg, synth.make_weights(cfg, 0))
+    rng = np.random.default_rng(5)
+    n = 100003
+    lt, lp, lb = (rng.normal(-3.0, 0.7, n).astype(np.float32) for _ in range(3))
+    adv = rng.normal(0.0, 1.0, n).astype(np.float32)
+    mask = (rng.random(n) < 0.8).astype(np.uint8)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    for m in (None, mask):
+        (total, n_clip, n_cnt), obj = eng.ppo_objective(dev(lt), dev(lp), dev(lb), dev(adv), 0.2,
+                                                        mask=None if m is None else dev(m), per_token=True)
+        want_total, want_obj, want_clip = trainer_side.decoupled_ppo_objective(lt, lp, lb, adv, 0.2, mask=m)
+        assert np.abs(obj.cpu().numpy() - want_obj).max() <= 1e-4 * max(1.0, np.abs(want_obj).max())
+        assert abs(total - want_total) <= 1e-5 * np.abs(want_obj).sum()
+        assert n_cnt == (n if m is None else int(m.sum()))
+        assert abs(n_clip - int(want_clip.sum())) <= 3          # ties at the clip edge may round either way
+    (total, n_clip, n_cnt), _ = eng.ppo_objective(dev(lt[:0]), dev(lp[:0]), dev(lb[:0]), dev(adv[:0]), 0.2)
+    assert (total, n_clip, n_cnt) == (0.0, 0, 0)
+    eng.close()

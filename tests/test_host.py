@@ -220,3 +220,28 @@ def test_kvalloc_shared_prefix_refcounts():
     assert L.areal_kvalloc_reserve(a, 3, 160) == binding.E_NOMEM         # per-sequence limit 8 blocks
     assert L.areal_kvalloc_reserve(a, 3, 128) == 0 and len(set(_table(L, a, 3))) == 8
     L.areal_kvalloc_destroy(a)
+
+
+def test_dynamic_batching_matches_oracle():
+    """Algorithm 1 in the library against the oracle on random length sets
+    (ties in length and in sequence count included) and on the edge cases."""
+    from oracle import trainer_side
+    L = binding.lib()
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        n = int(rng.integers(0, 60))
+        lens = rng.integers(1, 30, size=n).astype(np.int32)
+        cap, k = int(rng.integers(10, 90)), int(rng.integers(1, 7))
+        out = np.full(n, -1, dtype=np.int32)
+        nb = L.areal_dynamic_batching(n, lens.ctypes.data_as(binding._I32P), cap, k,
+                                      out.ctypes.data_as(binding._I32P))
+        want = trainer_side.dynamic_batching(lens, cap, k)
+        assert nb == len(want)
+        for b, members in enumerate(want):
+            assert sorted(np.nonzero(out == b)[0].tolist()) == sorted(members)
+    bad = np.array([3, 0], dtype=np.int32)
+    o = np.zeros(2, dtype=np.int32)
+    assert L.areal_dynamic_batching(2, bad.ctypes.data_as(binding._I32P), 10, 1,
+                                    o.ctypes.data_as(binding._I32P)) == binding.E_INVAL
+    assert L.areal_dynamic_batching(2, bad.ctypes.data_as(binding._I32P), 0, 1,
+                                    o.ctypes.data_as(binding._I32P)) == binding.E_INVAL
