@@ -29,6 +29,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 / bf16
+SHAPE_LABEL = {"qwen2-1.5b": "Qwen2-1.5B", "qwen2-7b": "Qwen2-7B", "tiny": "tiny"}
 # HBM bytes the decode attention kernel moves per algorithmic K/V byte, from rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs calibrated with a plain copy (profiles/attn_decode_kernel_hbm_traffic.md)
 ATTN_DECODE_FETCH_OVER_ALGORITHMIC = 1.024
@@ -496,7 +497,7 @@ def main():
                         unit="GB/s", frac=None, traffic=None, launches_timed=int(pn),
                         avg_launch_us=round(pms / max(pn, 1) * 1e3, 2))
     out = {
-        "metric": "gen tokens/s, 1 MI355X, Qwen2-1.5B shape; decode HBM GB/s % of peak",
+        "metric": f"gen tokens/s, 1 MI355X, {SHAPE_LABEL.get(wl['shape'], wl['shape'])} shape; decode HBM GB/s % of peak",
         "value": round(gen / total_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(total_s * 1e3 / args.steps, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
