@@ -18,7 +18,9 @@
  * Conventions
  *  - Plain C ABI, no exceptions, no abort.  Every call returns AREAL_OK (0)
  *    or a negative error code; areal_last_error() gives the text.  A call
- *    that fails leaves the context as it was before the call.
+ *    that fails leaves the context as it was before the call; the exception
+ *    is AREAL_E_HIP (the runtime itself failed): the context is then only
+ *    good for areal_destroy.
  *  - "device" pointers are HIP device memory owned by the caller (in the
  *    tests and benchmark: PyTorch allocations); "host" pointers are ordinary
  *    process memory, read or written before the call returns.
@@ -26,6 +28,11 @@
  *    hip_stream) in call order.  Calls return without waiting for the GPU;
  *    outputs in device memory are valid once the stream reaches that point.
  *  - One context serves one GPU and is not thread safe.
+ *  - Launch-shape tuning knobs are read from the environment when a context
+ *    is created (AREAL_DECODE_SPLIT_TARGET, AREAL_DECODE_MIN_CHUNK) or on
+ *    first use (AREAL_GEMM_MAX_SPLITS, AREAL_PREFILL_TILE_ROWS); unset, the
+ *    measured optima apply.  They change timings, never results beyond
+ *    float32 summation order.
  *  - Matrices are row-major, out-features major: y = x W^T with W [out, in].
  *  - The model is the Qwen2 family: pre-norm blocks, RMSNorm, rotary position
  *    embedding in rotate-half pairing, grouped-query causal attention,
