@@ -77,15 +77,6 @@ def decode_step_bytes(cfg, ctx_sum, n):
     return 2 * w_elems + kv_token * ctx_sum + kv_token * n + 2 * 4 * n * V
 
 
-def prefill_flops(cfg, lens):
-    H, F, V, L = cfg["hidden"], cfg["ffn"], cfg["vocab"], cfg["n_layers"]
-    qd, kd = cfg["n_q_heads"] * cfg["head_dim"], cfg["n_kv_heads"] * cfg["head_dim"]
-    p_layers = L * (qd * H + 2 * kd * H + H * qd + 3 * F * H)
-    lens = np.asarray(lens, dtype=np.float64)
-    return float(2 * p_layers * lens.sum() + 2 * V * H * len(lens)
-                 + 4 * qd * L * (lens * (lens + 1) / 2).sum())
-
-
 def prefill_work(cfg, prompts):
     """Rows and flops the library really computes for one areal_prefill call over
     `prompts`: a prompt equal to an earlier one of the call shares that one's full
