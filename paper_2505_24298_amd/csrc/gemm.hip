@@ -434,7 +434,7 @@ hipError_t run_dma(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, 
   splits = (nk + sps - 1) / sps;
   const int grid = grid_blocks(m_tiles, n_tiles, splits);
   gemm_dma_kernel<BM, BN, WM, WN, STAGES, MODE><<<grid, WM * WN * 64, 0, s>>>(
-      A, W, C, M, N, K, ldc, m_tiles, n_tiles, sps, splits > 1 ? 1 : 0);
+      A, W, C, M, N, K, ldc, m_tiles, n_tiles, sps, (splits > 1 || MODE == GEMM_ADD_F32) ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -450,10 +450,10 @@ hipError_t run(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, int 
   const int grid = grid_blocks(m_tiles, n_tiles, splits);
   if (K % BK)
     gemm_kernel<BM, BN, WM, WN, MODE, true><<<grid, WM * WN * 64, 0, s>>>(A, W, C, M, N, K, ldc, m_tiles,
-                                                                          n_tiles, sps, splits > 1 ? 1 : 0);
+                                                                          n_tiles, sps, (splits > 1 || MODE == GEMM_ADD_F32) ? 1 : 0);
   else
     gemm_kernel<BM, BN, WM, WN, MODE, false><<<grid, WM * WN * 64, 0, s>>>(A, W, C, M, N, K, ldc, m_tiles,
-                                                                           n_tiles, sps, splits > 1 ? 1 : 0);
+                                                                           n_tiles, sps, (splits > 1 || MODE == GEMM_ADD_F32) ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -513,8 +513,14 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
   } else if (M > 256) {                // prefill: MFMA-bound, large tiles
     const int t256 = (mode == GEMM_SWIGLU_F16 ? (N + 127) / 128 : (N + 255) / 256) * ((M + 255) / 256);
     if (t256 >= 224) { *cfg = 16; *splits = 1; return; }
-    if (mode == GEMM_ADD_F32 && K >= 4096) { *cfg = 16; *splits = 2; return; }
-    *cfg = 8; *splits = 1;
+    const int t128 = n_tiles * ((M + 127) / 128);
+    if (mode == GEMM_ADD_F32 && K >= 4096) {             // down projection: 6 column tiles of 256
+      if (t256 >= 128) { *cfg = 16; *splits = 1; }       // 8192 rows: 745 TFLOP/s
+      else { *cfg = 8; *splits = 2; }
+      return;
+    }
+    *cfg = 8;                                            // O projection and the like
+    *splits = (mode == GEMM_ADD_F32 && t128 <= 256) ? 2 : 1;
     return;
   } else if (n_tiles >= 100) {         // wide outputs: one work-group per column panel
     if (M <= 32) { c = 12; bm = 32; }
