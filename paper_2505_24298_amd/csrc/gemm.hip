@@ -480,13 +480,15 @@ hipError_t dispatch(hipStream_t s, int cfg, const f16* A, const GemmW& W, void* 
     case 15: return run_dma<128, 128, 2, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 16: return run_dma<256, 256, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 17: return run_dma<256, 128, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 18: return run_dma<256, 256, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 19: return run_dma<256, 256, 2, 4, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
     default: return hipErrorInvalidValue;
   }
 }
 
 }  // namespace
 
-int gemm_num_configs() { return 18; }
+int gemm_num_configs() { return 20; }
 
 // Tile configuration and K split for a product of this shape: rules read off
 // sweeps over every configuration on the MI355X at the decoder's shapes
@@ -512,10 +514,10 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     else { c = 0; bm = 128; }
   } else if (M > 256) {                // prefill: MFMA-bound, large tiles
     const int t256 = (mode == GEMM_SWIGLU_F16 ? (N + 127) / 128 : (N + 255) / 256) * ((M + 255) / 256);
-    if (t256 >= 224) { *cfg = 16; *splits = 1; return; }
+    if (t256 >= 224) { *cfg = 19; *splits = 1; return; }     // 256x256, 8 waves: 940 TFLOP/s
     const int t128 = n_tiles * ((M + 127) / 128);
     if (mode == GEMM_ADD_F32 && K >= 4096) {             // down projection: 6 column tiles of 256
-      if (t256 >= 128) { *cfg = 16; *splits = 1; }       // 8192 rows: 745 TFLOP/s
+      if (t256 >= 128) { *cfg = 19; *splits = 1; }       // 8192 rows: 780 TFLOP/s
       else { *cfg = 8; *splits = 2; }
       return;
     }
