@@ -482,13 +482,15 @@ hipError_t dispatch(hipStream_t s, int cfg, const f16* A, const GemmW& W, void* 
     case 17: return run_dma<256, 128, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 18: return run_dma<256, 256, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 19: return run_dma<256, 256, 2, 4, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 20: return run_dma<128, 128, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 21: return run_dma<128, 128, 4, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
     default: return hipErrorInvalidValue;
   }
 }
 
 }  // namespace
 
-int gemm_num_configs() { return 20; }
+int gemm_num_configs() { return 22; }
 
 // Tile configuration and K split for a product of this shape: rules read off
 // sweeps over every configuration on the MI355X at the decoder's shapes
@@ -527,12 +529,12 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
   } else if (n_tiles >= 100) {         // wide outputs: one work-group per column panel
     if (M <= 32) { c = 12; bm = 32; }
     else if (M <= 64) { c = 10; bm = 64; }
-    else if (M <= 128) { c = 7; bm = 128; }
-    else { c = 8; bm = 128; }          // two 128-row work-groups per CU beat one 256-row tile
+    else if (M <= 128) { c = 21; bm = 128; }
+    else { c = 20; bm = 128; }         // two 128-row work-groups per CU beat one 256-row tile
   } else {                             // narrow outputs: small row tiles + K split
     if (M <= 64 || K < 4096) { c = 12; bm = 32; }
     else if (M <= 128) { c = 10; bm = 64; }
-    else { c = 7; bm = 128; }
+    else { c = 21; bm = 128; }
   }
   int sp = 1;
   if (mode != GEMM_SWIGLU_F16 && M <= 256) {
