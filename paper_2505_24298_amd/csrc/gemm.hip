@@ -484,13 +484,19 @@ hipError_t dispatch(hipStream_t s, int cfg, const f16* A, const GemmW& W, void* 
     case 19: return run_dma<256, 256, 2, 4, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 20: return run_dma<128, 128, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 21: return run_dma<128, 128, 4, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 22:   // one 32-column panel per wave: no room for a gate/up pair
+      if constexpr (MODE != GEMM_SWIGLU_F16) return run_dma<32, 128, 1, 4, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+      else return hipErrorInvalidValue;
+    case 23:
+      if constexpr (MODE != GEMM_SWIGLU_F16) return run_dma<64, 128, 2, 4, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
+      else return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
 }
 
 }  // namespace
 
-int gemm_num_configs() { return 22; }
+int gemm_num_configs() { return 24; }
 
 // Tile configuration and K split for a product of this shape: rules read off
 // sweeps over every configuration on the MI355X at the decoder's shapes
@@ -532,9 +538,11 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     else if (M <= 128) { c = 21; bm = 128; }
     else { c = 20; bm = 128; }         // two 128-row work-groups per CU beat one 256-row tile
   } else {                             // narrow outputs: small row tiles + K split
-    if (M <= 64 || K < 4096) { c = 12; bm = 32; }
-    else if (M <= 128) { c = 10; bm = 64; }
+    if (M <= 64 || K < 4096) { c = 22; bm = 32; }          // four waves, a 32-column panel each
+    else if (M <= 128) { c = 23; bm = 64; }
     else { c = 21; bm = 128; }
+    if (mode == GEMM_SWIGLU_F16 && c == 22) c = 12;         // a gate/up pair needs 64 columns per wave
+    if (mode == GEMM_SWIGLU_F16 && c == 23) c = 10;
   }
   int sp = 1;
   if (mode != GEMM_SWIGLU_F16 && M <= 256) {
