@@ -537,6 +537,8 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     else if (M <= 64) { c = 10; bm = 64; }
     else if (M <= 128) { c = 21; bm = 128; }
     else { c = 20; bm = 128; }         // two 128-row work-groups per CU beat one 256-row tile
+    if (mode != GEMM_SWIGLU_F16 && c == 12) c = 22;       // output projection: one more wave pair
+    if (mode != GEMM_SWIGLU_F16 && c == 10) c = 23;
   } else {                             // narrow outputs: small row tiles + K split
     if (M <= 64 || K < 4096) { c = 22; bm = 32; }          // four waves, a 32-column panel each
     else if (M <= 128) { c = 23; bm = 64; }
