@@ -220,19 +220,23 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   __shared__ float so[4][16][D];
   __shared__ float s_new[16], v_new[D];
   const int i = blockIdx.z, kvh = blockIdx.y, split = blockIdx.x;
-  const int pos = rm.pos[i];
-  const int t0 = split * chunk;
-  if (t0 > pos) return;
-  const bool owner = pos < t0 + chunk;                 // this split holds the appended position
-  const int t1 = min(pos, t0 + chunk);                 // cached tokens [t0, t1)
-  const int b0 = t0 / kBlockTokens, b1 = (t1 + kBlockTokens - 1) / kBlockTokens;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, j = lane & 15;
   const int nkv = geom.n_kv_heads, G = nq / nkv;
+  const int t0 = split * chunk;
+  const int b0 = t0 / kBlockTokens;
+  // the table entries of the whole split are requested at once with the row's position (entries
+  // past the sequence's last block are stale but inside the table row, and never used)
   const int32_t* table = st.table + (int64_t)rm.slot[i] * st.max_blocks;
+  const int b_cap = min(b0 + chunk / kBlockTokens, st.max_blocks);
   BlockIds ids;
-  ids.lo = b0 + lane < b1 ? table[b0 + lane] : 0;
-  ids.hi = b0 + 64 + lane < b1 ? table[b0 + 64 + lane] : 0;
+  ids.lo = b0 + lane < b_cap ? table[b0 + lane] : 0;
+  ids.hi = b0 + 64 + lane < b_cap ? table[b0 + 64 + lane] : 0;
+  const int pos = rm.pos[i];
+  if (t0 > pos) return;
+  const bool owner = pos < t0 + chunk;                 // this split holds the appended position
+  const int t1 = min(pos, t0 + chunk);                 // cached tokens [t0, t1)
+  const int b1 = (t1 + kBlockTokens - 1) / kBlockTokens;
 
   // Loads go out in dependency order (the query row needs nothing, the angles need pos,
   // the K/V tiles need the block ids) and the rotation runs while the tiles are in flight.
@@ -336,36 +340,46 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
 }
 
 // Combine the split partials of one (row, head): out = sum_s O_s 2^(M_s-M) / sum_s L_s 2^(M_s-M).
-// Lane s of each wave fetches (M_s, L_s), so the statistics cost one round trip
-// and two wave reductions; the O_s rows are then fetched four splits at a time.
+// Every load address depends only on the launch shape, so the row's position, the
+// statistics (lane s fetches (M_s, L_s)) and the first eight partial rows all go out
+// together; which splits really exist (ns) is applied afterwards by selection.  Slots of
+// splits beyond ns hold stale values of earlier launches: selected away, never multiplied.
 template <int D>
 __global__ __launch_bounds__(D < 64 ? 64 : D) void attn_merge_kernel(const float* __restrict__ part_o,
                                                        const float* __restrict__ part_ml, RowMeta rm,
                                                        int nq, int chunk, int n_splits,
                                                        f16* __restrict__ out) {
+  constexpr int BATCH = 8;
   const int i = blockIdx.x / nq;
-  const int ctx = rm.pos[i] + 1;
-  const int ns = min(n_splits, (ctx + chunk - 1) / chunk);   // <= 32 < lanes of a wave
   const int64_t base = (int64_t)blockIdx.x * n_splits;
   const int lane = threadIdx.x & 63;
-  float ms = -INFINITY, ls = 0.f;
-  if (lane < ns) {
-    const float2 ml = *reinterpret_cast<const float2*>(part_ml + (base + lane) * 2);
-    ms = ml.x;
-    ls = ml.y;
-  }
+  const int dd = min((int)threadIdx.x, D - 1);
+  const float* po = part_o + base * D + dd;
+  const int pos = rm.pos[i];
+  float2 ml = {0.f, 0.f};
+  if (lane < n_splits) ml = *reinterpret_cast<const float2*>(part_ml + (base + lane) * 2);
+  float v[BATCH], vn[BATCH];
+#pragma unroll
+  for (int u = 0; u < BATCH; ++u) v[u] = u < n_splits ? po[(int64_t)u * D] : 0.f;
+
+  const int ns = min(n_splits, (pos + chunk) / chunk);      // splits of this row: ceil((pos+1)/chunk) <= 32
+  const float ms = lane < ns ? ml.x : -INFINITY, ls = lane < ns ? ml.y : 0.f;
   const float M = wave_max(ms);                               // whole waves only: blockDim >= 64
   const float sc = __builtin_amdgcn_exp2f(ms - M);           // lanes >= ns: 2^-inf = 0
   const float L = wave_sum(ls * sc);
-  const int dd = min((int)threadIdx.x, D - 1);
-  const float* po = part_o + base * D + dd;
   float O = 0.f;
-  for (int s0 = 0; s0 < ns; s0 += 4) {
-    float v[4];
+  for (int s0 = 0; s0 < ns; s0 += BATCH) {
+    if (s0 + BATCH < ns) {                                    // next batch in flight while this one is used
 #pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = s0 + u < ns ? po[(int64_t)(s0 + u) * D] : 0.f;
+      for (int u = 0; u < BATCH; ++u) vn[u] = s0 + BATCH + u < n_splits ? po[(int64_t)(s0 + BATCH + u) * D] : 0.f;
+    }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) O += v[u] * __shfl(sc, (s0 + u) & 31);
+    for (int u = 0; u < BATCH; ++u) {
+      const float w = __shfl(sc, (s0 + u) & 31);
+      O += s0 + u < ns ? v[u] * w : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) v[u] = vn[u];
   }
   if (threadIdx.x < D) out[(int64_t)blockIdx.x * D + dd] = f2h(O / L);
 }
