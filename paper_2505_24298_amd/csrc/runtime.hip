@@ -328,8 +328,11 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
     f16* arena_l = arena + (int64_t)l * c->geom.layer_stride;
     {
       ProfScope ps(c, AREAL_K_RMSNORM, l, sampled, rows);
-      // the QKV product may split K and accumulate atomically: clear its output here
-      HIP_TRY(c, launch_rmsnorm(s, h, w.norm_attn[l], xn, a.M, H, g.rms_eps, nullptr, qkv, qd + 2 * kd));
+      // the QKV product may split K and accumulate atomically: then its output is cleared here
+      int qkv_cfg, qkv_splits;
+      gemm_choose(a.M, qd + 2 * kd, H, GEMM_STORE_F32, &qkv_cfg, &qkv_splits);
+      HIP_TRY(c, launch_rmsnorm(s, h, w.norm_attn[l], xn, a.M, H, g.rms_eps, nullptr,
+                                qkv_splits > 1 ? qkv : nullptr, qd + 2 * kd));
     }
     {
       ProfScope ps(c, AREAL_K_GEMM_QKV, l, sampled, rows);
