@@ -209,3 +209,18 @@ def test_tiny_deep_context_many_splits(torch, binding):
     worst = max(float(np.abs(g - r).max()) for g, r in zip(got, ref))
     print(f"tiny/deep: logits {worst:.2e}")
     assert worst <= LOGIT_TOL
+
+
+@pytest.mark.parametrize("nq,nkv,d", [(4, 2, 64), (2, 2, 32), (16, 1, 32), (14, 2, 64), (8, 1, 128)])
+def test_head_geometries(torch, binding, nq, nkv, d):
+    """Head dimensions 32 / 64 / 128 and query-per-KV-head groups of 1, 2, 7, 8
+    and 16 (every attention template and row-group count): prompts long enough
+    for several prefill tiles and KV splits, an interrupt in the middle."""
+    cfg = synth.shape("tiny", n_q_heads=nq, n_kv_heads=nkv, head_dim=d, hidden=128, ffn=192)
+    w = synth.random_gains(synth.make_weights(cfg, 40 + nq, qkv_bias=True, std=0.04), 7)
+    w2 = synth.perturb_weights(w, 1003, scale=5e-3, round_bf16=False)
+    prompts = synth.make_prompts(cfg, 3, 1, 30, 330, seed=nq + d)
+    dl, dlb, dlf = _teacher_forced_run(torch, binding, cfg, w, prompts, 12, qkv_bias=True, interrupt=(5, w2),
+                                       max_batch_tokens=96, kv_blocks=96)
+    print(f"heads {nq}/{nkv} d{d}: logits {dl:.2e}  logp_behav {dlb:.2e}  logp_full {dlf:.2e}")
+    assert dl <= LOGIT_TOL and dlb <= LOGP_TOL and dlf <= LOGP_TOL
