@@ -224,3 +224,15 @@ def test_head_geometries(torch, binding, nq, nkv, d):
                                        max_batch_tokens=96, kv_blocks=96)
     print(f"heads {nq}/{nkv} d{d}: logits {dl:.2e}  logp_behav {dlb:.2e}  logp_full {dlf:.2e}")
     assert dl <= LOGIT_TOL and dlb <= LOGP_TOL and dlf <= LOGP_TOL
+
+
+@pytest.mark.parametrize("hidden,ffn", [(200, 344), (4608, 320), (8192, 192)])
+def test_hidden_sizes(torch, binding, hidden, ffn):
+    """Hidden sizes off the 64-wide K slabs (register-staged GEMM path for every
+    product) and in the two widest RMSNorm variants (rows of 4608 and 8192)."""
+    cfg = synth.shape("tiny", hidden=hidden, ffn=ffn, n_layers=1)
+    w = synth.random_gains(synth.make_weights(cfg, 50, std=0.02), 8)
+    prompts = synth.make_prompts(cfg, 2, 1, 20, 70, seed=hidden)
+    dl, dlb, dlf = _teacher_forced_run(torch, binding, cfg, w, prompts, 6, max_batch_tokens=64, kv_blocks=16)
+    print(f"hidden {hidden}: logits {dl:.2e}  logp_behav {dlb:.2e}  logp_full {dlf:.2e}")
+    assert dl <= LOGIT_TOL and dlb <= LOGP_TOL and dlf <= LOGP_TOL
