@@ -358,11 +358,12 @@ def op_gemm(A, W0, W1, C_out, mode, cfg=-1, splits=-1):
         raise ArealError(rc, "areal_op_gemm")
 
 
-def weights_to_device(w, device="cuda:0", bf16=True):
+def weights_to_device(w, device="cuda:0", bf16=True, f16=False):
     """numpy weight dict (synth.make_weights) -> dict of torch device tensors.
-    With bf16 the values must already be bf16-representable (exact cast)."""
+    With bf16 the values must already be bf16-representable (exact cast); f16
+    rounds to half precision (the layout a context without convert_weights takes)."""
     import torch
-    dt = torch.bfloat16 if bf16 else torch.float32
+    dt = torch.float16 if f16 else (torch.bfloat16 if bf16 else torch.float32)
 
     def cv(a):
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device=device, dtype=dt).contiguous()

@@ -284,3 +284,39 @@ def test_shared_prompt_prefix_with_interrupt_and_early_termination(torch, bindin
         eng.free_seq(s)
     assert eng.kv_blocks() == (40, 40)
     eng.close()
+
+
+def test_half_precision_weights_in_place_and_tied_output_projection(torch, binding):
+    """A context without the conversion workspace reads fp16 parameter sets where
+    they are (also across a weight update); the output projection may be the
+    embedding matrix itself; bf16 sets are refused by such a context."""
+    from oracle import rollout
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 61, qkv_bias=True)
+    w["lm_head"] = w["embed"]                                     # tied
+    w2 = synth.perturb_weights(w, 1004, scale=5e-3, round_bf16=False)
+    w2["lm_head"] = w2["embed"]
+    eng = binding.Areal(cfg, max_seqs=4, max_seq_len=96, max_batch_tokens=64, kv_blocks=24,
+                        convert_weights=False)
+    with pytest.raises(binding.ArealError) as e:
+        eng.load_weights(binding.weights_to_device(w, bf16=False), 0)     # float32 needs the workspace
+    assert e.value.code == binding.E_INVAL
+    dw = binding.weights_to_device(w, f16=True)
+    dw["lm_head"] = dw["embed"]                                   # the same device tensor
+    eng.load_weights(dw, 0)
+    wk = rollout.RolloutWorker(cfg, _f16_weights(w), version=0, seed=0)
+    prompts = synth.make_prompts(cfg, 3, 1, 10, 40, seed=13)
+    ids = [0, 1, 2]
+    for s, p in zip(ids, prompts):
+        wk.add(s, p)
+    logits = eng.prefill(ids, prompts)
+    for step in range(10):
+        toks = _check_step(torch, eng, wk, ids, logits)
+        logits = eng.decode_step(ids, toks)
+        if step == 4:
+            dw2 = binding.weights_to_device(w2, f16=True)
+            dw2["lm_head"] = dw2["embed"]
+            wk.update_weights(_f16_weights(w2), 1)
+            _, logits, _ = eng.update_weights_interrupt(dw2, 1)
+    _check_step(torch, eng, wk, ids, logits)
+    eng.close()
