@@ -26,6 +26,10 @@ extern "C" {
 int areal_op_gemm(void* hip_stream, const void* A, const void* W0, const void* W1, void* C,
                   int32_t M, int32_t N, int32_t K, int32_t mode, int32_t cfg, int32_t splits);
 int areal_op_gemm_num_configs(void);
+/* The tile configuration and K split the library takes for a product of this
+ * shape and mode (host only, no GPU call).  0 or AREAL_E_INVAL. */
+int areal_op_gemm_choose(int32_t M, int32_t N, int32_t K, int32_t mode, int32_t* cfg_out,
+                         int32_t* splits_out);
 
 #ifdef __cplusplus
 }

@@ -89,6 +89,7 @@ _SIGNATURES = {
     "areal_op_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                 C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "areal_op_gemm_num_configs": (C.c_int, []),
+    "areal_op_gemm_choose": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _I32P, _I32P]),
     # include/areal_host.h
     "areal_kvalloc_create": (C.c_void_p, [C.c_int64, C.c_int32, C.c_int32]),
     "areal_kvalloc_destroy": (None, [C.c_void_p]),

@@ -511,6 +511,21 @@ static int max_splits() {
   return v;
 }
 
+// Largest K split that keeps every XCD at one round of work-groups (32 CUs, one
+// work-group each): units of (column tile, split) go to the XCDs round-robin, each with
+// m_tiles work-groups.  Each split keeps at least 3 slabs.  Beyond 8 (12 with a single
+// row tile) the atomic adds outweigh the shorter K walk.
+static int split_for(int M, int bm, int n_tiles, int nk) {
+  const int m_tiles = (M + bm - 1) / bm;
+  const int cap = std::min(std::max(1, nk / 3), std::min(m_tiles == 1 ? 12 : 8, max_splits()));
+  static const int steps[] = {12, 8, 6, 4, 3, 2, 1};
+  for (int cand : steps) {
+    if (cand > cap) continue;
+    if (((n_tiles * cand + 7) / 8) * m_tiles <= 32 || cand == 1) return cand;
+  }
+  return 1;
+}
+
 void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
   const bool dma_ok = (K % BK) == 0;
   const int n_tiles = mode == GEMM_SWIGLU_F16 ? (N + 63) / 64 : (N + 127) / 128;
@@ -539,27 +554,40 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     else { c = 20; bm = 128; }         // two 128-row work-groups per CU beat one 256-row tile
     if (mode != GEMM_SWIGLU_F16 && c == 12) c = 22;       // output projection: one more wave pair
     if (mode != GEMM_SWIGLU_F16 && c == 10) c = 23;
-  } else {                             // narrow outputs: small row tiles + K split
-    if (M <= 64 || K < 4096) { c = 22; bm = 32; }          // four waves, a 32-column panel each
-    else if (M <= 128) { c = 23; bm = 64; }
+    // gate/up with a long K (7B shape, 56 slabs): the register-staged tiles come out 8-10 % ahead
+    if (mode == GEMM_SWIGLU_F16 && K >= 3072 && c == 12) c = 4;
+    if (mode == GEMM_SWIGLU_F16 && K >= 3072 && c == 10) c = 6;
+  } else if (mode == GEMM_SWIGLU_F16) { // narrow gate/up (small models): no K split
+    if (M <= 32) { c = 12; bm = 32; }
+    else if (M <= 64) { c = 10; bm = 64; }
     else { c = 21; bm = 128; }
-    if (mode == GEMM_SWIGLU_F16 && c == 22) c = 12;         // a gate/up pair needs 64 columns per wave
-    if (mode == GEMM_SWIGLU_F16 && c == 23) c = 10;
+  } else {
+    // Narrow outputs (QKV, O, down): row tiles of 32 / 64 / 128 with a K split.  Every
+    // (tile height, split) with the split no larger than what keeps each XCD at one round
+    // of work-groups is priced in microseconds -- a fixed part, the K slabs one work-group
+    // walks, and the atomic adds of all splits -- with constants fitted to the sweeps at
+    // the 1.5B and 7B shapes; the cheapest wins.
+    static const int cand_cfg[3] = {22, 23, 21}, cand_bm[3] = {32, 64, 128};
+    static const float slab_us[3] = {0.38f, 0.55f, 0.75f}, fixed_us[3] = {2.f, 2.f, 3.f};
+    const float atomic_us = 3.3e-6f * (float)M * (float)N;        // per split
+    static const int steps[] = {12, 8, 6, 4, 3, 2, 1};
+    float best = 1e30f;
+    c = 22; bm = 32;
+    int best_sp = 1;
+    for (int k = 0; k < 3; ++k) {
+      const int sp_max = split_for(M, cand_bm[k], n_tiles, nk);
+      for (int sp_k : steps) {
+        if (sp_k > sp_max) continue;
+        const float cost = fixed_us[k] + (float)((nk + sp_k - 1) / sp_k) * slab_us[k] + atomic_us * (float)sp_k;
+        if (cost < best) { best = cost; c = cand_cfg[k]; bm = cand_bm[k]; best_sp = sp_k; }
+      }
+    }
+    *cfg = c;
+    *splits = best_sp;
+    return;
   }
   int sp = 1;
-  if (mode != GEMM_SWIGLU_F16 && M <= 256) {
-    // Largest split that keeps every XCD at one round of work-groups (32 CUs, one
-    // work-group each): units of (column tile, split) go to the XCDs round-robin, each
-    // with m_tiles work-groups.  Each split keeps at least 3 slabs.  Beyond 8 (12 with a
-    // single row tile) the atomic adds outweigh the shorter K walk.
-    const int m_tiles = (M + bm - 1) / bm;
-    const int cap = std::min(std::max(1, nk / 3), std::min(m_tiles == 1 ? 12 : 8, max_splits()));
-    static const int steps[] = {12, 8, 6, 4, 3, 2, 1};
-    for (int cand : steps) {
-      if (cand > cap) continue;
-      if (((n_tiles * cand + 7) / 8) * m_tiles <= 32 || cand == 1) { sp = cand; break; }
-    }
-  }
+  if (mode != GEMM_SWIGLU_F16 && M <= 256) sp = split_for(M, bm, n_tiles, nk);
   *cfg = c;
   *splits = sp;
 }

@@ -1014,6 +1014,14 @@ int areal_op_gemm(void* stream, const void* A, const void* W0, const void* W1, v
   return e == hipSuccess ? AREAL_OK : AREAL_E_HIP;
 }
 int areal_op_gemm_num_configs(void) { return gemm_num_configs(); }
+int areal_op_gemm_choose(int32_t M, int32_t N, int32_t K, int32_t mode, int32_t* cfg_out, int32_t* splits_out) {
+  if (M <= 0 || N <= 0 || K <= 0 || mode < 0 || mode > 2 || !cfg_out || !splits_out) return AREAL_E_INVAL;
+  int c, sp;
+  gemm_choose(M, N, K, (GemmMode)mode, &c, &sp);
+  *cfg_out = c;
+  *splits_out = sp;
+  return AREAL_OK;
+}
 
 // ---- host-only test surface (include/areal_host.h) ---------------------------
 struct areal_kvalloc { KvAllocator a; };

@@ -8,7 +8,8 @@
       time and bandwidth (HIP events inside the library) and the step time.
   python3 paper_2505_24298_amd/microbench.py gemm [M,M,...] [shape,...]
       every tile configuration x K split of the projection GEMM at the decoder's
-      shapes (qkv, o, gateup, down, lmhead of the 1.5B shape); weights rotate over
+      shapes (qkv, o, gateup, down, lmhead of the 1.5B shape; qkv7 ... lmhead7 of the 7B shape);
+      weights rotate over
       > 1 GB so they come from HBM.
   python3 paper_2505_24298_amd/microbench.py prefill [qwen2-1.5b|qwen2-7b]
       prefill of 32x256, 8x2048, 4x8000 tokens: per-kernel time of one layer.
@@ -76,7 +77,10 @@ def gemm(ms_arg, shapes_arg):
     L = binding.lib()
     ncfg = L.areal_op_gemm_num_configs()
     shapes = {"qkv": (2048, 1536, 0), "o": (1536, 1536, 1), "gateup": (8960, 1536, 2),
-              "down": (1536, 8960, 1), "lmhead": (151936, 1536, 0)}
+              "down": (1536, 8960, 1), "lmhead": (151936, 1536, 0),
+              # the 7B shape
+              "qkv7": (4608, 3584, 0), "o7": (3584, 3584, 1), "gateup7": (18944, 3584, 2),
+              "down7": (3584, 18944, 1), "lmhead7": (152064, 3584, 0)}
     Ms = [int(x) for x in ms_arg.split(",")]
     g = torch.Generator(device="cuda").manual_seed(0)
     for name in shapes_arg.split(","):
@@ -93,7 +97,7 @@ def gemm(ms_arg, shapes_arg):
             Cs = [torch.zeros((M, N), device="cuda", dtype=torch.float16 if mode == 2 else torch.float32)
                   for _ in range(ncopy)]
             for cfg in range(ncfg):
-                for splits in ([1] if mode == 2 or name == "lmhead" else [1, 2, 3, 4, 6, 8, 12]):
+                for splits in ([1] if mode == 2 or name.startswith("lmhead") else [1, 2, 3, 4, 6, 8, 12]):
                     if cfg >= 7 and K % 64:
                         continue
                     iters = 3 * ncopy if wbytes < 1e8 else 6
