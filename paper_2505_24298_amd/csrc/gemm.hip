@@ -557,6 +557,7 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     // gate/up with a long K (7B shape, 56 slabs): the register-staged tiles come out 8-10 % ahead
     if (mode == GEMM_SWIGLU_F16 && K >= 3072 && c == 12) c = 4;
     if (mode == GEMM_SWIGLU_F16 && K >= 3072 && c == 10) c = 6;
+    if (mode == GEMM_SWIGLU_F16 && K >= 3072 && c == 21) c = 20;
   } else if (mode == GEMM_SWIGLU_F16) { // narrow gate/up (small models): no K split
     if (M <= 32) { c = 12; bm = 32; }
     else if (M <= 64) { c = 10; bm = 64; }
