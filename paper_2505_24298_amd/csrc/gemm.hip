@@ -538,14 +538,15 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
   } else if (M > 256) {                // prefill: MFMA-bound, large tiles
     const int t256 = (mode == GEMM_SWIGLU_F16 ? (N + 127) / 128 : (N + 255) / 256) * ((M + 255) / 256);
     if (t256 >= 224) { *cfg = 19; *splits = 1; return; }     // 256x256, 8 waves: 940 TFLOP/s
-    const int t128 = n_tiles * ((M + 127) / 128);
-    if (mode == GEMM_ADD_F32 && K >= 4096) {             // down projection: 6 column tiles of 256
-      if (t256 >= 128) { *cfg = 19; *splits = 1; }       // 8192 rows: 780 TFLOP/s
-      else { *cfg = 8; *splits = 2; }
+    if (mode == GEMM_ADD_F32 && K >= 4096) {             // down projection: few column tiles, long K
+      if (t256 >= 128) { *cfg = 19; *splits = 1; }       // 8192 rows: 760-980 TFLOP/s
+      else if (t256 >= 64) { *cfg = 19; *splits = 2; }
+      else { *cfg = 20; *splits = 2; }
       return;
     }
-    *cfg = 8;                                            // O projection and the like
-    *splits = (mode == GEMM_ADD_F32 && t128 <= 256) ? 2 : 1;
+    const int t128 = n_tiles * ((M + 127) / 128);
+    if (t128 > 256) { *cfg = 20; *splits = 1; return; }  // O projection at 8192 rows
+    *cfg = 21; *splits = 1;                              // a last, short pass: 128x128, 8 waves, 3 stages
     return;
   } else if (n_tiles >= 100) {         // wide outputs: one work-group per column panel
     if (M <= 32) { c = 12; bm = 32; }
@@ -554,6 +555,7 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
     else { c = 20; bm = 128; }         // two 128-row work-groups per CU beat one 256-row tile
     if (mode != GEMM_SWIGLU_F16 && c == 12) c = 22;       // output projection: one more wave pair
     if (mode != GEMM_SWIGLU_F16 && c == 10) c = 23;
+    if (mode != GEMM_SWIGLU_F16 && c == 20) { c = 19; bm = 256; }   // output projection above 128 rows
     // gate/up with a long K (7B shape, 56 slabs): the register-staged tiles come out 8-10 % ahead
     if (mode == GEMM_SWIGLU_F16 && K >= 3072 && c == 12) c = 4;
     if (mode == GEMM_SWIGLU_F16 && K >= 3072 && c == 10) c = 6;
