@@ -41,7 +41,10 @@ __device__ __forceinline__ float sexp(float x) {
   return x < -25.0f ? 0.0f : w;
 }
 __device__ __forceinline__ u64 mass_of(float z, float m) {
-  return (u64)(sexp(z - m) * 4294967296.0f);
+  // floor(w * 2^32) for w in [0, 1]: the product is exact (power-of-two scale); below 2^32 it
+  // fits the 32-bit truncating conversion, and only w = 1 gives 2^32 itself
+  const float w = sexp(z - m);
+  return w >= 1.0f ? (1ull << 32) : (u64)__float2uint_rz(w * 4294967296.0f);
 }
 
 // ---- Philox4x32-10 (Salmon et al., SC'11) ----------------------------------
