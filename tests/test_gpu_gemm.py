@@ -12,7 +12,8 @@ def _ref(A, W):
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (37, 344, 128), (200, 1000, 344), (256, 1536, 1536),
-                                   (300, 2048, 1000), (130, 520, 8960)])
+                                   (300, 2048, 1000), (130, 520, 8960),
+                                   (5000, 1100, 512)])   # more than 8 row tiles: the super-tile block map
 def test_gemm_all_configs(M, N, K):
     NO_SWIGLU = (22, 23)      # one 32-column panel per wave: no gate/up pair in a wave
     import torch
