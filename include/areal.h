@@ -194,6 +194,23 @@ int areal_update_weights_interrupt(areal_ctx* ctx, const areal_weights* new_w,
                                    int32_t* live_seq_ids_out, float* logits_out,
                                    int64_t* reprefilled_tokens_out);
 
+/* Proposition 1 (the behaviour policy of an interrupted trajectory is defined
+ * position by position): a weight update usually lands between
+ * areal_sample_logprob and the areal_decode_step that would consume the sampled
+ * tokens.  Those tokens were drawn from the old version's logits and must carry
+ * the old version's tag.  areal_append_tokens appends tokens_in[i] to sequence
+ * seq_ids[i] with that tag and NO forward pass (history and block table only);
+ * the areal_update_weights_interrupt that follows recomputes every prefix, the
+ * appended position included, under the new parameters and returns the logits
+ * for the token after it.  Until that call the sequence has a position without
+ * K/V: areal_decode_step on it fails with AREAL_E_STATE.  (Without this call
+ * the order sample -> update -> decode would tag the token with the new
+ * version: append, or decode, before updating.)
+ *   seq_ids host [n] live, distinct; tokens_in device int32 [n].
+ * Errors as areal_decode_step; n == 0 is a no-op. */
+int areal_append_tokens(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
+                        const int32_t* tokens_in);
+
 /* Section 5.2, Eq. 5 (decoupled PPO objective): the proximal policy's token
  * log-probabilities are recomputed over complete trajectories, with whatever
  * parameters are loaded now, when a training batch has arrived.  For each
@@ -266,7 +283,8 @@ int areal_adopt_seq(areal_ctx* ctx, int32_t seq_id, int32_t len, int32_t fill_to
 #define AREAL_K_GEMM_DOWN 8
 #define AREAL_K_GEMM_LMHEAD 9
 #define AREAL_K_SAMPLER 10
-#define AREAL_K_COUNT 11
+#define AREAL_K_ATTN_MERGE 11
+#define AREAL_K_COUNT 12
 int areal_profile_begin(areal_ctx* ctx, int32_t kernel_class, int32_t layer, int32_t every);
 int areal_profile_end(areal_ctx* ctx, int64_t* n_samples_out, double* total_ms_out,
                       double* total_units_out);

@@ -18,7 +18,7 @@ OK, E_INVAL, E_NOMEM, E_STATE, E_HIP = 0, -1, -2, -3, -4
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 KV_BLOCK_TOKENS = 16
 (K_EMBED, K_RMSNORM, K_GEMM_QKV, K_ROPE_KVWRITE, K_ATTN_DECODE, K_ATTN_PREFILL, K_GEMM_O,
- K_GEMM_GATEUP, K_GEMM_DOWN, K_GEMM_LMHEAD, K_SAMPLER) = range(11)
+ K_GEMM_GATEUP, K_GEMM_DOWN, K_GEMM_LMHEAD, K_SAMPLER, K_ATTN_MERGE) = range(12)
 
 
 class ArealError(RuntimeError):
@@ -61,6 +61,7 @@ _SIGNATURES = {
     "areal_load_weights": (C.c_int, [C.c_void_p, C.POINTER(Weights), C.c_uint64]),
     "areal_prefill": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _I32P, _I32P, C.c_void_p]),
     "areal_decode_step": (C.c_int, [C.c_void_p, C.c_int32, _I32P, C.c_void_p, C.c_void_p]),
+    "areal_append_tokens": (C.c_int, [C.c_void_p, C.c_int32, _I32P, C.c_void_p]),
     "areal_sample_logprob": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, _I32P, _I32P, C.c_float,
                                        C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p]),
@@ -291,6 +292,12 @@ class Areal:
         self._check(self.L.areal_decode_step(self.ctx, len(ids), ids_p, tokens_in.data_ptr(),
                                              logits_out.data_ptr()))
         return logits_out
+
+    def append_tokens(self, seq_ids, tokens_in):
+        torch = self.torch
+        ids, ids_p = _i32(seq_ids)
+        assert tokens_in.is_cuda and tokens_in.dtype == torch.int32 and tokens_in.numel() >= len(ids)
+        self._check(self.L.areal_append_tokens(self.ctx, len(ids), ids_p, tokens_in.data_ptr()))
 
     def sample_logprob(self, logits, seq_ids, positions, temperature=1.0, top_p=1.0, seed=0,
                        forced_tokens=None, out=None):

@@ -189,14 +189,14 @@ __device__ __forceinline__ void rotate(RawHead<D>& r, const f16* __restrict__ bi
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float x1 = r.x[c][e], x2 = r.x[c + HC][e];
-        out[c][e] = f2h(x1 * a.c[c][e] - x2 * a.s[c][e]);
-        out[c + HC][e] = f2h(x2 * a.c[c][e] + x1 * a.s[c][e]);
+        out[c][e] = f2h_sat(x1 * a.c[c][e] - x2 * a.s[c][e]);
+        out[c + HC][e] = f2h_sat(x2 * a.c[c][e] + x1 * a.s[c][e]);
       }
   } else {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float xp = __shfl_xor(r.x[0][e], 32);
-      out[0][e] = f2h(g < 2 ? r.x[0][e] * a.c[0][e] - xp * a.s[0][e] : r.x[0][e] * a.c[0][e] + xp * a.s[0][e]);
+      out[0][e] = f2h_sat(g < 2 ? r.x[0][e] * a.c[0][e] - xp * a.s[0][e] : r.x[0][e] * a.c[0][e] + xp * a.s[0][e]);
     }
   }
 }
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     for (int dim = lane; dim < D; dim += 64) {
       float v = vrow[dim];
       if (bv) v += h2f(bv[kvh * D + dim]);
-      const f16 hv = f2h(v);
+      const f16 hv = f2h_sat(v);
       v_new[dim] = h2f(hv);
       vt[v_tile_index(D, tin, dim)] = hv;
     }
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     }
     const int head = kvh * G + h;
     if (n_splits == 1) {
-      out[((int64_t)i * nq + head) * D + dd] = f2h(O / L);
+      out[((int64_t)i * nq + head) * D + dd] = f2h_sat(O / L);
     } else {
       const int64_t pi = ((int64_t)i * nq + head) * n_splits + split;
       part_o[pi * D + dd] = O;
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(D < 64 ? 64 : D) void attn_merge_kernel(const float
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) v[u] = vn[u];
   }
-  if (threadIdx.x < D) out[(int64_t)blockIdx.x * D + dd] = f2h(O / L);
+  if (threadIdx.x < D) out[(int64_t)blockIdx.x * D + dd] = f2h_sat(O / L);
 }
 
 // ----------------------------------------------------------------- prefill
@@ -605,7 +605,7 @@ __global__ __launch_bounds__(256, (D == 128 && RGW == 3) ? 2 : 1) void attn_pref
         f16* op = out + ((int64_t)(wk.row0 + row_in) * nq + head) * D;
         const float inv = 1.0f / lo[v];
 #pragma unroll
-        for (int n = 0; n < D / 16; ++n) op[16 * n + j] = f2h(o[r][n][v] * inv);
+        for (int n = 0; n < D / 16; ++n) op[16 * n + j] = f2h_sat(o[r][n][v] * inv);
       }
     }
   }
@@ -634,16 +634,30 @@ hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm
 #define AREAL_DEC(DD)                                                                              \
   attn_decode_kernel<DD><<<grid, 256, 0, s>>>(qkv, rm, st, bq, bk, bv, cos_tab, sin_tab,           \
                                                arena_layer, geom, n_q_heads, chunk, n_splits,      \
-                                               scale_log2, part_o, part_ml, out);                  \
-  if (n_splits > 1)                                                                                \
-    attn_merge_kernel<DD><<<M * n_q_heads, DD < 64 ? 64 : DD, 0, s>>>(part_o, part_ml, rm,         \
-                                                                      n_q_heads, chunk, n_splits, out);
+                                               scale_log2, part_o, part_ml, out);
   switch (geom.head_dim) {
     case 32: AREAL_DEC(32) break;
     case 64: AREAL_DEC(64) break;
     default: AREAL_DEC(128) break;
   }
 #undef AREAL_DEC
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_merge(hipStream_t s, int M, RowMeta rm, int head_dim, int n_q_heads, int chunk,
+                             int n_splits, const float* part_o, const float* part_ml, f16* out) {
+  if (M <= 0 || n_splits < 2 || n_splits > 32 || chunk <= 0 || !part_o || !part_ml || !out ||
+      (head_dim != 32 && head_dim != 64 && head_dim != 128))
+    return hipErrorInvalidValue;
+#define AREAL_MRG(DD)                                                                              \
+  attn_merge_kernel<DD><<<M * n_q_heads, DD < 64 ? 64 : DD, 0, s>>>(part_o, part_ml, rm, n_q_heads, \
+                                                                    chunk, n_splits, out);
+  switch (head_dim) {
+    case 32: AREAL_MRG(32) break;
+    case 64: AREAL_MRG(64) break;
+    default: AREAL_MRG(128) break;
+  }
+#undef AREAL_MRG
   return hipGetLastError();
 }
 

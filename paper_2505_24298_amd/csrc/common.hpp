@@ -22,6 +22,11 @@ constexpr int kBlockTokens = 16;   // tokens per KV block
 
 __device__ __forceinline__ float h2f(f16 x) { return (float)x; }
 __device__ __forceinline__ f16 f2h(float x) { return (f16)x; }   // round to nearest even
+// Activations and K/V on their way to the matrix cores: magnitudes beyond the half range
+// saturate to +-65504 instead of turning into infinities (NaN stays NaN).
+__device__ __forceinline__ f16 f2h_sat(float x) {
+  return (f16)__builtin_amdgcn_fmed3f(x, -65504.0f, 65504.0f);
+}
 
 // 16-byte global load of 8 halves
 __device__ __forceinline__ f16x8 ld8(const f16* p) { return *reinterpret_cast<const f16x8*>(p); }

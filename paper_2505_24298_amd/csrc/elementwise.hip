@@ -79,7 +79,7 @@ __global__ __launch_bounds__(64) void rmsnorm_kernel(const float* __restrict__ x
       const f16x4 g = *reinterpret_cast<const f16x4*>(gain + c);
       f16x4 o;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) o[k] = f2h(v[i][k] * r * h2f(g[k]));
+      for (int k = 0; k < 4; ++k) o[k] = f2h_sat(v[i][k] * r * h2f(g[k]));
       *reinterpret_cast<f16x4*>(yp + c) = o;
     }
   }
@@ -129,12 +129,12 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(
     const float y1 = x1 * c - x2 * sv, y2 = x2 * c + x1 * sv;
     if (head < nq) {
       f16* qo = q_out + ((int64_t)r * nq + head) * d;
-      qo[j] = f2h(y1);
-      qo[j + half] = f2h(y2);
+      qo[j] = f2h_sat(y1);
+      qo[j + half] = f2h_sat(y2);
     } else {
       f16* kt = arena_layer + kv_tile_off(geom, blk, head - nq, 0);
-      kt[k_tile_index(tin, j)] = f2h(y1);
-      kt[k_tile_index(tin, j + half)] = f2h(y2);
+      kt[k_tile_index(tin, j)] = f2h_sat(y1);
+      kt[k_tile_index(tin, j + half)] = f2h_sat(y2);
     }
   }
   const float* vrow = row + (nq + nkv) * d;
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(
     float v = vrow[idx];
     if (bv) v += h2f(bv[idx]);
     f16* vt = arena_layer + kv_tile_off(geom, blk, kvh, 1);
-    vt[v_tile_index(d, tin, dim)] = f2h(v);
+    vt[v_tile_index(d, tin, dim)] = f2h_sat(v);
   }
 }
 
@@ -154,6 +154,28 @@ hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta r
   if (M <= 0 || geom.head_dim % 16 || (bq && (!bk || !bv))) return hipErrorInvalidValue;
   rope_kvwrite_kernel<<<M, 256, 0, s>>>(qkv, rm, st, bq, bk, bv, cos_tab, sin_tab, q_out, arena_layer,
                                         geom, n_q_heads);
+  return hipGetLastError();
+}
+
+// A sampled token joins its sequence without a forward pass (the weights change before
+// the pass that would have taken it as input): history entry and, at a block start, the
+// block the host reserved.
+__global__ __launch_bounds__(256) void append_kernel(int n, int V, RowMeta rm,
+                                                     const int32_t* __restrict__ tokens_in,
+                                                     const int32_t* __restrict__ new_block, SeqState st) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= n) return;
+  const int slot = rm.slot[r], pos = rm.pos[r];
+  int tok = tokens_in[r];
+  tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+  st.hist[(int64_t)slot * st.max_seq_len + pos] = tok;
+  const int nb = new_block[r];
+  if (nb >= 0) st.table[(int64_t)slot * st.max_blocks + pos / kBlockTokens] = nb;
+}
+hipError_t launch_append(hipStream_t s, int n, int vocab, RowMeta rm, const int32_t* tokens_in,
+                         const int32_t* new_block, SeqState st) {
+  if (n <= 0 || vocab <= 0 || !tokens_in || !new_block) return hipErrorInvalidValue;
+  append_kernel<<<(n + 255) / 256, 256, 0, s>>>(n, vocab, rm, tokens_in, new_block, st);
   return hipGetLastError();
 }
 

@@ -216,7 +216,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const f16* __restric
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
           if (m < M && f < N)
-            C[(int64_t)m * ldc + f] = f2h(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
+            C[(int64_t)m * ldc + f] = f2h_sat(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
         }
       }
   } else {
@@ -396,7 +396,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
           if (m < M && f < N)
-            C[(int64_t)m * ldc + f] = f2h(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
+            C[(int64_t)m * ldc + f] = f2h_sat(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
         }
       }
   } else {

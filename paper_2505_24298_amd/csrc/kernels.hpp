@@ -29,6 +29,10 @@ hipError_t launch_rope_kvwrite(hipStream_t s, const float* qkv, int M, RowMeta r
                                const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                                const float* sin_tab, f16* q_out, f16* arena_layer, KvGeom geom,
                                int n_q_heads);
+// rows (rm.slot[r], rm.pos[r]): history[slot][pos] = tokens_in[r]; new_block[r] >= 0 is installed
+// as block pos/16 of the slot
+hipError_t launch_append(hipStream_t s, int n, int vocab, RowMeta rm, const int32_t* tokens_in,
+                         const int32_t* new_block, SeqState st);
 // {slot, block index, block id} triples -> block table; {dst slot, src slot, n tokens} -> history
 hipError_t launch_table_patch(hipStream_t s, const int32_t* patch, int n, SeqState st);
 hipError_t launch_hist_copy(hipStream_t s, const int32_t* jobs, int n, SeqState st);
@@ -66,12 +70,14 @@ int attn_prefill_tile_rows(int n_q_heads, int n_kv_heads);   // 16 or 32
 // QKV rows [M, (nq + 2 nkv) d] of the pass: bias, RoPE and rounding of q and of the appended
 // token's k happen inside, and the appended k, v are stored into the sequence's block
 // (table entry pos/16 must be installed).  Context = positions 0 .. pos.  `chunk` tokens per
-// split (multiple of 128, at most 2048); with n_splits > 1 the partials go through
-// `part_o` / `part_ml` and a merge kernel.
+// split (multiple of 128, at most 2048); with n_splits > 1 the partials go to
+// `part_o` / `part_ml` and launch_attn_merge combines them into `out`.
 hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
                               const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                               const float* sin_tab, f16* arena_layer, KvGeom geom, int n_q_heads,
                               int chunk, int n_splits, float* part_o, float* part_ml, f16* out);
+hipError_t launch_attn_merge(hipStream_t s, int M, RowMeta rm, int head_dim, int n_q_heads, int chunk,
+                             int n_splits, const float* part_o, const float* part_ml, f16* out);
 hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work, int n_work,
                                SeqState st, const f16* arena_layer, KvGeom geom, int n_q_heads,
                                f16* out);

@@ -96,6 +96,7 @@ Layout make_layout(const areal_model_cfg& c) {
 struct SeqInfo {
   bool live = false;
   int32_t len = 0;
+  int32_t kv_len = 0;                   // positions whose K/V is in the cache (< len after areal_append_tokens)
   int32_t n_shared = 0;                 // leading KV blocks held together with other sequences
   int64_t pending_version = 0;          // version whose logits the next token is sampled from
   std::vector<int64_t> versions;        // per position; -1 = prompt
@@ -343,10 +344,17 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
               *bv = w.has_bias ? w.bv[l] : nullptr;
     if (a.decode) {
       // bias, RoPE and the store of the appended K/V are part of the attention kernel
-      ProfScope ps(c, AREAL_K_ATTN_DECODE, l, sampled, a.attn_units);
-      HIP_TRY(c, launch_attn_decode(s, qkv, a.M, a.rm, st, bq, bk, bv, cos_t, sin_t, arena_l, c->geom, nq,
-                                    a.chunk, a.n_splits, c->wsp<float>(c->lay.part_o),
-                                    c->wsp<float>(c->lay.part_ml), attn));
+      {
+        ProfScope ps(c, AREAL_K_ATTN_DECODE, l, sampled, a.attn_units);
+        HIP_TRY(c, launch_attn_decode(s, qkv, a.M, a.rm, st, bq, bk, bv, cos_t, sin_t, arena_l, c->geom, nq,
+                                      a.chunk, a.n_splits, c->wsp<float>(c->lay.part_o),
+                                      c->wsp<float>(c->lay.part_ml), attn));
+      }
+      if (a.n_splits > 1) {
+        ProfScope ps(c, AREAL_K_ATTN_MERGE, l, sampled, rows);
+        HIP_TRY(c, launch_attn_merge(s, a.M, a.rm, d, nq, a.chunk, a.n_splits, c->wsp<float>(c->lay.part_o),
+                                     c->wsp<float>(c->lay.part_ml), attn));
+      }
     } else {
       {
         ProfScope ps(c, AREAL_K_ROPE_KVWRITE, l, sampled, rows);
@@ -548,7 +556,7 @@ int areal_create(const areal_model_cfg* cfg, areal_ctx** out) {
   }
   if (const char* e = getenv("AREAL_DECODE_MIN_CHUNK")) {
     const int v = atoi(e);
-    if (v == 128 || v == 256 || v == 384 || v == 512) c->min_chunk = v;
+    if (v >= 128 && v <= 2048 && v % 128 == 0) c->min_chunk = v;
   }
   c->lay = lay;
   c->stream = reinterpret_cast<hipStream_t>(cfg->hip_stream);
@@ -689,6 +697,7 @@ int areal_prefill(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t
     SeqInfo& s = c->seqs[id];
     s.live = true;
     s.len = len;
+    s.kv_len = len;
     s.n_shared = std::max(s.n_shared, n_sh[i]);
     s.pending_version = c->version;
     s.versions.assign(len, -1);
@@ -722,6 +731,8 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
     const int id = seq_ids[i];
     if (id < 0 || id >= g.max_seqs || seen[id]) return fail(c, AREAL_E_INVAL, "sequence id out of range or repeated");
     if (!c->seqs[id].live) return fail(c, AREAL_E_STATE, "decode on a sequence that was not prefilled");
+    if (c->seqs[id].kv_len != c->seqs[id].len)
+      return fail(c, AREAL_E_STATE, "sequence holds appended tokens without K/V: areal_update_weights_interrupt comes first");
     seen[id] = 1;
     if (c->seqs[id].len + 1 > g.max_seq_len) return fail(c, AREAL_E_NOMEM, "sequence would exceed max_seq_len");
     need_blocks += c->alloc->extra_needed(id, c->seqs[id].len + 1);
@@ -746,6 +757,7 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
     hnb[i] = c->alloc->blocks(id).size() > had ? c->alloc->blocks(id).back() : -1;
     s.versions.push_back(s.pending_version);
     s.len = pos + 1;
+    s.kv_len = pos + 1;
     s.pending_version = c->version;
     sum_ctx += pos + 1;
     max_ctx = std::max(max_ctx, pos + 1);
@@ -776,6 +788,48 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
   a.logits = logits_out;
   a.attn_units = (double)sum_ctx;
   return run_pass(c, a);
+}
+
+int areal_append_tokens(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t* tokens_in) {
+  if (!c) return AREAL_E_INVAL;
+  if (n == 0) return AREAL_OK;
+  if (n < 0 || !seq_ids || !tokens_in) return fail(c, AREAL_E_INVAL, "NULL argument or negative count");
+  const areal_model_cfg& g = c->cfg;
+  if (n > g.max_seqs) return fail(c, AREAL_E_INVAL, "more rows than max_seqs");
+  std::vector<char> seen(g.max_seqs, 0);
+  int64_t need_blocks = 0;
+  for (int i = 0; i < n; ++i) {
+    const int id = seq_ids[i];
+    if (id < 0 || id >= g.max_seqs || seen[id]) return fail(c, AREAL_E_INVAL, "sequence id out of range or repeated");
+    if (!c->seqs[id].live) return fail(c, AREAL_E_STATE, "append to a sequence that was not prefilled");
+    seen[id] = 1;
+    if (c->seqs[id].len + 1 > g.max_seq_len) return fail(c, AREAL_E_NOMEM, "sequence would exceed max_seq_len");
+    need_blocks += c->alloc->extra_needed(id, c->seqs[id].len + 1);
+  }
+  if (need_blocks > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
+  int rc = ring_begin(c, align_up((uint64_t)n * 4, 64) * 3);
+  if (rc) return rc;
+  const uint64_t start = c->seg_used;
+  Staged s_slot = ring_take(c, (uint64_t)n * 4), s_pos = ring_take(c, (uint64_t)n * 4),
+         s_nb = ring_take(c, (uint64_t)n * 4);
+  int32_t *hslot = (int32_t*)s_slot.host, *hpos = (int32_t*)s_pos.host, *hnb = (int32_t*)s_nb.host;
+  for (int i = 0; i < n; ++i) {
+    const int id = seq_ids[i];
+    SeqInfo& s = c->seqs[id];
+    const int pos = s.len;
+    const size_t had = c->alloc->blocks(id).size();
+    c->alloc->reserve(id, pos + 1);
+    hslot[i] = id;
+    hpos[i] = pos;
+    hnb[i] = c->alloc->blocks(id).size() > had ? c->alloc->blocks(id).back() : -1;
+    s.versions.push_back(s.pending_version);      // the version whose logits the token was drawn from
+    s.len = pos + 1;                              // kv_len stays: no K/V for this position yet
+  }
+  rc = ring_flush(c, start);
+  if (rc) return rc;
+  HIP_TRY(c, launch_append(c->stream, n, g.vocab, RowMeta{(const int32_t*)s_slot.dev, (const int32_t*)s_pos.dev},
+                           tokens_in, (const int32_t*)s_nb.dev, c->seq_state()));
+  return AREAL_OK;
 }
 
 int areal_sample_logprob(areal_ctx* c, int32_t n, const float* logits, const int32_t* seq_ids,
@@ -840,6 +894,7 @@ int areal_update_weights_interrupt(areal_ctx* c, const areal_weights* new_w, uin
   for (int i = 0; i < nl; ++i) {
     live_ids_out[i] = spans[i].slot;
     c->seqs[spans[i].slot].pending_version = c->version;
+    c->seqs[spans[i].slot].kv_len = c->seqs[spans[i].slot].len;
   }
   if (retok_out) *retok_out = total;
   if (nl == 0) return AREAL_OK;
@@ -969,6 +1024,7 @@ int areal_adopt_seq(areal_ctx* c, int32_t id, int32_t len, int32_t fill_token) {
   SeqInfo& s = c->seqs[id];
   s.live = true;
   s.len = len;
+  s.kv_len = len;
   s.pending_version = c->version;
   s.versions.assign(len, -1);
   return AREAL_OK;

@@ -31,7 +31,7 @@ import numpy as np
 
 
 def _weights(torch, cfg):
-    from bench import device_weights
+    from paper_2505_24298_amd.harness import device_weights
     return device_weights(torch, cfg, 0, "cuda:0")
 
 

@@ -24,7 +24,7 @@ def _to_oracle(w):
 
 def test_qwen2_1p5b_shape_slice_with_interrupt():
     import torch
-    from bench import device_weights
+    from paper_2505_24298_amd.harness import device_weights
     from oracle import decoder, sampler
     from paper_2505_24298_amd import binding
     cfg = synth.shape("qwen2-1.5b")
@@ -137,7 +137,7 @@ def test_bench_launch_configuration_sampled_sequences():
     recomputes three sampled sequences one by one: logits after the prompt and
     after each of two forced decode steps."""
     import torch
-    from bench import device_weights
+    from paper_2505_24298_amd.harness import device_weights
     from oracle import decoder
     from paper_2505_24298_amd import binding
     cfg, wl, prompts, out_lens = synth.make_workload("qwen2-1.5b-rollout")
@@ -187,7 +187,7 @@ def test_qwen2_7b_full_depth_slice():
     of 40-64 tokens, 4 forced decode steps.  The oracle reads the same bf16
     values as float32 arrays (its arithmetic is float64)."""
     import torch
-    from bench import device_weights
+    from paper_2505_24298_amd.harness import device_weights
     from oracle import decoder, sampler
     from paper_2505_24298_amd import binding
     cfg = synth.shape("qwen2-7b")

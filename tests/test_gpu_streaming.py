@@ -2,10 +2,13 @@
 staleness gate, weight update + interrupt per finished training batch) on the
 tiny shape: every trajectory is generated to its full length, the number of
 weight updates is the number of training batches, the synchronous schedule
-(eta = 0) never overlaps batches, and a larger eta needs fewer decode steps."""
+(eta = 0) never overlaps batches, a larger eta needs fewer decode steps, and for
+every eta the run takes exactly the ticks of the oracle's plain event loop, with
+every request submitted and completed under the versions that loop gives it."""
 import numpy as np
 import pytest
 
+from oracle import staleness
 from paper_2505_24298_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -13,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 def _run(eta, n_total=48, slots=8, train_batch=8):
     import torch
-    from bench import streaming_rollout
+    from paper_2505_24298_amd.harness import streaming_rollout
     from paper_2505_24298_amd import binding
     cfg = synth.shape("tiny")
     w0 = synth.make_weights(cfg, 0)
@@ -30,6 +33,10 @@ def _run(eta, n_total=48, slots=8, train_batch=8):
     eng.close()
     assert r["gen_tokens"] == int(outs.sum())
     assert r["interrupts"] == n_total // train_batch
+    # Section 5.1: the same stream through the oracle's controller, one request at a time
+    ticks, done = staleness.simulate_stream(n_total, train_batch, eta, slots, outs)
+    assert r["ticks"] == ticks
+    assert sorted(r["records"]) == sorted(done)
     return r, outs
 
 
@@ -42,3 +49,8 @@ def test_streaming_completes_every_trajectory():
     asyn, _ = _run(eta=3)
     assert asyn["decode_steps"] < sync["decode_steps"]
     assert asyn["mean_rows"] > sync["mean_rows"]
+
+
+@pytest.mark.parametrize("eta", [1, 2, 5])
+def test_streaming_matches_the_oracle_event_loop(eta):
+    _run(eta=eta)
