@@ -50,13 +50,14 @@ __device__ __forceinline__ void dma16(const void* src, void* dst_wave_base) {
 }
 
 __device__ __forceinline__ void wait_vmcnt(int n) {
-  // s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt = [15:14]:[3:0])
-  switch (n) {
+  // s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt = [15:14]:[3:0]); the counter
+  // has 6 bits, so a larger bound is tightened to 63
+  switch (n < 63 ? n : 63) {
 #define AREAL_W(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | 0x0F70); break;
-    AREAL_W(0) AREAL_W(1) AREAL_W(2) AREAL_W(3) AREAL_W(4) AREAL_W(5) AREAL_W(6) AREAL_W(7) AREAL_W(8)
-    AREAL_W(9) AREAL_W(10) AREAL_W(11) AREAL_W(12) AREAL_W(13) AREAL_W(14) AREAL_W(15) AREAL_W(16)
-    AREAL_W(18) AREAL_W(20) AREAL_W(21) AREAL_W(24) AREAL_W(27) AREAL_W(28) AREAL_W(30) AREAL_W(32)
-    AREAL_W(36) AREAL_W(40) AREAL_W(48)
+#define AREAL_W8(B) AREAL_W(B) AREAL_W(B + 1) AREAL_W(B + 2) AREAL_W(B + 3) AREAL_W(B + 4) AREAL_W(B + 5) \
+                    AREAL_W(B + 6) AREAL_W(B + 7)
+    AREAL_W8(0) AREAL_W8(8) AREAL_W8(16) AREAL_W8(24) AREAL_W8(32) AREAL_W8(40) AREAL_W8(48) AREAL_W8(56)
+#undef AREAL_W8
 #undef AREAL_W
     default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
   }

@@ -237,6 +237,42 @@ def test_weight_update_with_nothing_in_flight(torch, binding):
     eng.close()
 
 
+def test_pending_token_keeps_the_old_version_across_a_weight_update(torch, binding):
+    """A weight update that lands between sampling and the decode step: the sampled tokens
+    join their sequences through areal_append_tokens (old version tag, no forward pass), the
+    update recomputes every prefix with them, and the logits that follow are the oracle's
+    under the new weights.  A decode step on a sequence with an appended token and no
+    update is refused.  Sequences cross a KV-block boundary with the appended token."""
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 21)
+    w2 = synth.perturb_weights(w, 1002, scale=5e-3, round_bf16=False)
+    eng = _engine(binding, cfg, w)
+    wk = _oracle(cfg, w)
+    prompts = [np.arange(5, 5 + n, dtype=np.int32) for n in (16, 31, 9)]     # the 17th / 32nd token opens a block
+    ids = [0, 1, 2]
+    for s, p in zip(ids, prompts):
+        wk.add(s, p)
+    logits = eng.prefill(ids, prompts)
+    toks = _check_step(torch, eng, wk, ids, logits)              # sampled under version 0, not yet appended
+    free_before = eng.kv_blocks()[1]
+    eng.append_tokens(ids, toks)
+    assert eng.kv_blocks()[1] == free_before - 1                 # sequence 0 opened its second block
+    with pytest.raises(binding.ArealError) as e:
+        eng.decode_step(ids, toks)
+    assert e.value.code == binding.E_STATE
+    wk.update_weights(_f16_weights(w2), 3)
+    live, logits, retok = eng.update_weights_interrupt(binding.weights_to_device(w2, bf16=False), 3)
+    assert live.tolist() == ids and retok == sum(len(wk.tokens[s]) for s in ids)
+    for step in range(3):
+        toks = _check_step(torch, eng, wk, ids, logits.contiguous())
+        logits = eng.decode_step(ids, toks)
+    for s in ids:
+        assert eng.get_tokens(s).tolist() == wk.tokens[s]
+        v = eng.get_versions(s)
+        assert v[len(prompts[s]):].tolist() == [0, 3, 3, 3] == wk.versions[s]
+    eng.close()
+
+
 def test_shared_prompt_prefix_with_interrupt_and_early_termination(torch, binding):
     """Four samples of each of two prompts (lengths 37 and 48: the second ends on
     a block boundary) admitted in one call: the samples share the prompt's full
