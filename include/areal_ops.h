@@ -26,20 +26,6 @@ extern "C" {
 int areal_op_gemm(void* hip_stream, const void* A, const void* W0, const void* W1, void* C,
                   int32_t M, int32_t N, int32_t K, int32_t mode, int32_t cfg, int32_t splits);
 int areal_op_gemm_num_configs(void);
-
-/* The same product with the RMSNorm of its input taken apart, as the decode step of
- * areal_decode_step runs the QKV and gate/up projections at small row counts (the
- * normalisation of the decoder blocks' inputs, Qwen2 family, Section 2): the A operand is
- * half(X[m,k] * gain[k]) of float32 rows X [M,K] (the residual stream), formed inside the
- * kernel, and the row factor r_m = 1/sqrt(mean_k X[m,k]^2 + eps) comes after the product:
- *   mode 0: C float32 [M,N] = A W0^T, WITHOUT r_m (the consumer of C applies it)
- *   mode 2: C half    [M,N] = silu(r_m A W0^T) * (r_m A W1^T)
- * X float32 [M,K], gain half [K], W0/W1 half [N,K], 16-byte aligned, K % 64 == 0.
- * cfg 0 .. areal_op_gemm_x_num_configs()-1 or -1; splits as areal_op_gemm (mode 0 only). */
-int areal_op_gemm_x(void* hip_stream, const void* X, const void* gain, float eps, const void* W0,
-                    const void* W1, void* C, int32_t M, int32_t N, int32_t K, int32_t mode,
-                    int32_t cfg, int32_t splits);
-int areal_op_gemm_x_num_configs(void);
 /* The tile configuration and K split the library takes for a product of this
  * shape and mode (host only, no GPU call).  0 or AREAL_E_INVAL. */
 int areal_op_gemm_choose(int32_t M, int32_t N, int32_t K, int32_t mode, int32_t* cfg_out,

@@ -90,9 +90,6 @@ _SIGNATURES = {
     "areal_op_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                 C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "areal_op_gemm_num_configs": (C.c_int, []),
-    "areal_op_gemm_x": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
-                                  C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
-    "areal_op_gemm_x_num_configs": (C.c_int, []),
     "areal_op_gemm_choose": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _I32P, _I32P]),
     # include/areal_host.h
     "areal_kvalloc_create": (C.c_void_p, [C.c_int64, C.c_int32, C.c_int32]),
@@ -367,18 +364,6 @@ def op_gemm(A, W0, W1, C_out, mode, cfg=-1, splits=-1):
                              None if W1 is None else W1.data_ptr(), C_out.data_ptr(), M, N, K, mode, cfg, splits)
     if rc != OK:
         raise ArealError(rc, "areal_op_gemm")
-
-
-def op_gemm_x(X, gain, eps, W0, W1, C_out, mode, cfg=-1, splits=-1):
-    """areal_op_gemm_x on torch tensors (current stream)."""
-    import torch
-    M, K = X.shape
-    N = W0.shape[0]
-    rc = lib().areal_op_gemm_x(torch.cuda.current_stream().cuda_stream, X.data_ptr(), gain.data_ptr(), float(eps),
-                               W0.data_ptr(), None if W1 is None else W1.data_ptr(), C_out.data_ptr(), M, N, K,
-                               mode, cfg, splits)
-    if rc != OK:
-        raise ArealError(rc, "areal_op_gemm_x")
 
 
 def weights_to_device(w, device="cuda:0", bf16=True, f16=False):

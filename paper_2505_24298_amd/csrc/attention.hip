@@ -172,12 +172,8 @@ __device__ __forceinline__ void load_angles(RopeAngles<D>& a, const float* __res
   }
 }
 template <int D>
-__device__ __forceinline__ void rotate(RawHead<D>& r, float row_scale, const f16* __restrict__ bias,
-                                       const RopeAngles<D>& a, int g, f16x8 (&out)[D / 32]) {
-#pragma unroll
-  for (int c = 0; c < D / 32; ++c)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) r.x[c][e] *= row_scale;
+__device__ __forceinline__ void rotate(RawHead<D>& r, const f16* __restrict__ bias, const RopeAngles<D>& a,
+                                       int g, f16x8 (&out)[D / 32]) {
   if (bias) {
 #pragma unroll
     for (int c = 0; c < D / 32; ++c) {
@@ -219,11 +215,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     const f16* __restrict__ bk, const f16* __restrict__ bv, const float* __restrict__ cos_tab,
     const float* __restrict__ sin_tab, f16* __restrict__ arena, KvGeom geom, int nq, int chunk,
     int n_splits, float scale_log2, float* __restrict__ part_o, float* __restrict__ part_ml,
-    f16* __restrict__ out, const float* __restrict__ xres, int hidden, float eps) {
+    f16* __restrict__ out) {
   __shared__ float sm[4][16], sl[4][16];
   __shared__ float so[4][16][D];
   __shared__ float s_new[16], v_new[D];
-  __shared__ float s_ss[4];
   const int i = blockIdx.z, kvh = blockIdx.y, split = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, j = lane & 15;
@@ -257,25 +252,8 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   KvFrag<D> cur, nxt;
   if (b < b1) load_group_ids<D>(cur, arena, geom, ids, b0, b, b1, kvh, lane);
 
-  // The QKV row may come without its RMSNorm row factor (the projection ran on the
-  // un-normalised residual row times the gain): then every work-group of the row sums the
-  // squares of the residual row itself (a few KB, while the first tiles are in flight).
-  float row_scale = 1.0f;
-  if (xres) {
-    const float* xr = xres + (int64_t)i * hidden;
-    float ssq = 0.f;
-    for (int c = threadIdx.x * 4; c < hidden; c += 256 * 4) {
-      const f32x4 v4 = *reinterpret_cast<const f32x4*>(xr + c);
-      ssq += v4[0] * v4[0] + v4[1] * v4[1] + v4[2] * v4[2] + v4[3] * v4[3];
-    }
-    ssq = wave_sum(ssq);
-    if (lane == 0) s_ss[wave] = ssq;
-    __syncthreads();
-    row_scale = 1.0f / sqrtf((s_ss[0] + s_ss[1] + s_ss[2] + s_ss[3]) / (float)hidden + eps);
-  }
-
   f16x8 qf[D / 32];
-  rotate<D>(qraw, row_scale, bq ? bq + head * D : nullptr, ang, g, qf);
+  rotate<D>(qraw, bq ? bq + head * D : nullptr, ang, g, qf);
   if (j >= G) {
     const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -285,7 +263,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     RawHead<D> kraw;
     load_raw<D>(kraw, row + (nq + kvh) * D, g);
     f16x8 kf[D / 32];
-    rotate<D>(kraw, row_scale, bk ? bk + kvh * D : nullptr, ang, g, kf);
+    rotate<D>(kraw, bk ? bk + kvh * D : nullptr, ang, g, kf);
     float dot = 0.f;
 #pragma unroll
     for (int c = 0; c < D / 32; ++c)
@@ -303,7 +281,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     f16* vt = arena + kv_tile_off(geom, blk, kvh, 1);
     const float* vrow = row + (nq + nkv + kvh) * D;
     for (int dim = lane; dim < D; dim += 64) {
-      float v = vrow[dim] * row_scale;
+      float v = vrow[dim];
       if (bv) v += h2f(bv[kvh * D + dim]);
       const f16 hv = f2h_sat(v);
       v_new[dim] = h2f(hv);
@@ -645,9 +623,7 @@ static bool geom_ok(const KvGeom& g, int nq) {
 hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
                               const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                               const float* sin_tab, f16* arena_layer, KvGeom geom, int n_q_heads,
-                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out,
-                              const float* xres, int hidden, float eps) {
-  if (xres && (hidden <= 0 || hidden % 4 || ((uintptr_t)xres & 15) || !(eps >= 0.f))) return hipErrorInvalidValue;
+                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out) {
   if (M <= 0 || !geom_ok(geom, n_q_heads) || chunk <= 0 || chunk % (4 * NB * kBlockTokens) ||
       chunk > 128 * kBlockTokens || n_splits <= 0 || (n_splits > 1 && (!part_o || !part_ml)) ||
       !qkv || !cos_tab || !sin_tab || (bq && (!bk || !bv)) ||
@@ -658,7 +634,7 @@ hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm
 #define AREAL_DEC(DD)                                                                              \
   attn_decode_kernel<DD><<<grid, 256, 0, s>>>(qkv, rm, st, bq, bk, bv, cos_tab, sin_tab,           \
                                                arena_layer, geom, n_q_heads, chunk, n_splits,      \
-                                               scale_log2, part_o, part_ml, out, xres, hidden, eps);
+                                               scale_log2, part_o, part_ml, out);
   switch (geom.head_dim) {
     case 32: AREAL_DEC(32) break;
     case 64: AREAL_DEC(64) break;

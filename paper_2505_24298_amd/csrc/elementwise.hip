@@ -10,14 +10,8 @@ namespace areal {
 __global__ __launch_bounds__(256) void embed_kernel(const f16* __restrict__ E, int H, int V,
                                                     RowMeta rm, const int32_t* __restrict__ tokens_in,
                                                     const int32_t* __restrict__ new_block, SeqState st,
-                                                    float* __restrict__ h, float* __restrict__ zero_out,
-                                                    int zero_cols) {
+                                                    float* __restrict__ h) {
   const int r = blockIdx.x;
-  if (zero_out) {
-    float* zp = zero_out + (int64_t)r * zero_cols;
-    const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
-    for (int c = threadIdx.x * 4; c < zero_cols; c += 256 * 4) *reinterpret_cast<f32x4*>(zp + c) = z4;
-  }
   const int slot = rm.slot[r], pos = rm.pos[r];
   int tok;
   int32_t* hp = st.hist + (int64_t)slot * st.max_seq_len + pos;
@@ -44,10 +38,9 @@ __global__ __launch_bounds__(256) void embed_kernel(const f16* __restrict__ E, i
 }
 
 hipError_t launch_embed(hipStream_t s, const f16* embed, int hidden, int vocab, int M, RowMeta rm,
-                        const int32_t* tokens_in, const int32_t* new_block, SeqState st, float* h,
-                        float* zero_out, int zero_cols) {
-  if (M <= 0 || hidden % 8 || vocab <= 0 || (zero_out && zero_cols % 4)) return hipErrorInvalidValue;
-  embed_kernel<<<M, 256, 0, s>>>(embed, hidden, vocab, rm, tokens_in, new_block, st, h, zero_out, zero_cols);
+                        const int32_t* tokens_in, const int32_t* new_block, SeqState st, float* h) {
+  if (M <= 0 || hidden % 8 || vocab <= 0) return hipErrorInvalidValue;
+  embed_kernel<<<M, 256, 0, s>>>(embed, hidden, vocab, rm, tokens_in, new_block, st, h);
   return hipGetLastError();
 }
 

@@ -251,41 +251,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const f16* __restric
 // Requires K % 64 == 0.
 constexpr int GROUP_BYTES = 1024 + 128;   // 8 rows x 128 B, + 128 B skew between groups
 
-// ASRC = 0: A is half precision [M, K] and travels like W.
-// ASRC = 1: the A operand is RMSNorm(x) of float32 rows x [M, K] with the normalisation
-//   taken apart: the rows travel HBM -> LDS as float32 (groups of 4 rows x 256 B, 16-byte
-//   chunk q of row R at slot q ^ (R & 15)), the fragment reads multiply by the gain
-//   (one 128-byte gain slab per stage) and round to half, and the row factor
-//   1/sqrt(mean x^2 + eps), a scalar per output row, is applied after the product:
-//   GEMM_SWIGLU_F16 sums x^2 from the fragments it reads anyway (the work-group walks the
-//   whole row) and scales both accumulators in its epilogue; GEMM_STORE_F32 stores the
-//   unscaled product and leaves the factor to its consumer.  No separate RMSNorm kernel
-//   and no half-precision copy of the normalised rows.
-
-template <int BM, int BN, int WM, int WN, int STAGES, int MODE, int ASRC>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __restrict__ A, GemmX X, GemmW W,
+template <int BM, int BN, int WM, int WN, int STAGES, int MODE>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __restrict__ A, GemmW W,
                                                                 void* __restrict__ Cv, int M, int N,
                                                                 int K, int ldc, int m_tiles,
                                                                 int n_tiles, int slabs_per_split,
                                                                 int atomic) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int GA = ASRC ? BM / 4 : BM / 8, GB = BN / 8;   // load instructions (1 KiB each) per slab
-  constexpr int A_BYTES = ASRC ? BM * 256 : GA * GROUP_BYTES;
-  constexpr int G_BYTES = ASRC ? NW * 128 : 0;              // gain slab, one copy per wave
-  constexpr int LPS = (GA + GB) / NW + (ASRC ? 1 : 0);      // load instructions per wave per slab
-  static_assert(GB % NW == 0 && GA % NW == 0, "row groups must divide over the waves");
+  constexpr int GA = BM / 8, GB = BN / 8;              // row groups per slab
+  constexpr int LPS = (GA + GB) / NW;                  // load instructions per wave per slab
+  static_assert((GA + GB) % NW == 0 && GA % NW == 0, "row groups must divide over the waves");
   static_assert(MODE != GEMM_SWIGLU_F16 || (TN % 2 == 0), "SwiGLU needs gate+up in one wave tile");
-  static_assert(!ASRC || MODE != GEMM_ADD_F32, "fused-norm input serves the QKV and gate/up products");
-  constexpr int STAGE_BYTES = A_BYTES + GB * GROUP_BYTES + G_BYTES;
+  constexpr int STAGE_BYTES = (GA + GB) * GROUP_BYTES;
   __shared__ __attribute__((aligned(16))) char lds[STAGES * STAGE_BYTES];
-  __shared__ float row_ss[ASRC && MODE == GEMM_SWIGLU_F16 ? BM : 1];
 
-  if (X.zero) {                                         // stripes of float4 over the whole grid
-    const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
-    for (int i = (blockIdx.x * NW * 64 + threadIdx.x) * 4; i < X.zero_n; i += gridDim.x * NW * 64 * 4)
-      *reinterpret_cast<f32x4*>(X.zero + i) = z4;
-  }
   int tile_m, tile_n, split;
   if (!tile_of_block(blockIdx.x, m_tiles, n_tiles, tile_m, tile_n, split)) return;
 
@@ -293,45 +273,33 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
   const int wm = wave / WN, wn = wave % WN;
   const int m0 = tile_m * BM;
 
-  // this wave's share of the load instructions: GA/NW of A, then GB/NW of W (then the gain slab)
-  constexpr int LA = GA / NW, LB = GB / NW;
-  const char* src[LA + LB];
-  int dst_off[LA + LB];
+  // this wave's share of the row groups: GA/NW groups of A, then GB/NW of B
+  const f16* src[LPS];
+  int dst_off[LPS];
   {
+    const int rin = lane >> 3;                          // row inside the group
 #pragma unroll
-    for (int i = 0; i < LA + LB; ++i) {
-      const bool is_a = i < LA;
-      const int gi = is_a ? wave * LA + i : wave * LB + (i - LA);
-      if (is_a && ASRC) {
-        const int row = gi * 4 + (lane >> 4);           // 4 rows x 16 chunks of 4 floats
-        const int chunk = (lane & 15) ^ (row & 15);
+    for (int i = 0; i < LPS; ++i) {
+      const bool is_a = i < GA / NW;
+      const int gi = is_a ? wave * (GA / NW) + i : wave * (GB / NW) + (i - GA / NW);
+      const int row = gi * 8 + rin;
+      const int chunk = (lane & 7) ^ (row & 7);
+      if (is_a) {
         const int m = min(m0 + row, M - 1);
-        src[i] = reinterpret_cast<const char*>(X.x + (int64_t)m * K + chunk * 4);
-        dst_off[i] = gi * 1024;
+        src[i] = A + (int64_t)m * K + chunk * 8;
+        dst_off[i] = gi * GROUP_BYTES;
       } else {
-        const int row = gi * 8 + (lane >> 3);           // 8 rows x 8 chunks of 8 halves
-        const int chunk = (lane & 7) ^ (row & 7);
-        if (is_a) {
-          const int m = min(m0 + row, M - 1);
-          src[i] = reinterpret_cast<const char*>(A + (int64_t)m * K + chunk * 8);
-          dst_off[i] = gi * GROUP_BYTES;
-        } else {
-          const f16* p = w_row_ptr<BN, MODE>(W, tile_n, row, N, K);
-          if (!p) p = w_row_ptr<BN, MODE>(W, 0, 0, N, K);
-          src[i] = reinterpret_cast<const char*>(p + chunk * 8);
-          dst_off[i] = A_BYTES + gi * GROUP_BYTES;
-        }
+        const f16* p = w_row_ptr<BN, MODE>(W, tile_n, row, N, K);
+        if (!p) p = w_row_ptr<BN, MODE>(W, 0, 0, N, K);
+        src[i] = p + chunk * 8;
+        dst_off[i] = (GA + gi) * GROUP_BYTES;
       }
     }
   }
   auto issue = [&](int stage, int k0) {
 #pragma unroll
-    for (int i = 0; i < LA + LB; ++i)
-      dma16(src[i] + (int64_t)k0 * ((ASRC && i < LA) ? 4 : 2), lds + stage * STAGE_BYTES + dst_off[i]);
-    if (ASRC) {                                         // 64 gains = 8 lanes x 16 B, this wave's copy
-      char* gdst = lds + stage * STAGE_BYTES + A_BYTES + GB * GROUP_BYTES + wave * 128;
-      if (lane < 8) dma16(X.gain + k0 + lane * 8, gdst);
-    }
+    for (int i = 0; i < LPS; ++i)
+      dma16(src[i] + k0, lds + stage * STAGE_BYTES + dst_off[i]);
   };
 
   f32x16 acc[TM][TN];
@@ -344,50 +312,26 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
 
   const int fr = lane & 31, fh = lane >> 5;
   // fragment addressing: tile row R -> group R>>3, slot (R&7)*8 + (chunk ^ (R&7))
-  // (float32 rows: row R at R*256, 16-byte chunk q at slot q ^ (R&15))
-  int a_base[TM], a_x[TM], b_base[TN], koff[BK / 16];
+  int a_base[TM], b_base[TN], koff[BK / 16];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int R = wm * (BM / WM) + i * 32 + fr;
-    a_base[i] = ASRC ? R * 256 : (R >> 3) * GROUP_BYTES + (R & 7) * 128;
-    a_x[i] = R & 15;
+    a_base[i] = (R >> 3) * GROUP_BYTES + (R & 7) * 128;
   }
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int R = wn * (BN / WN) + j * 32 + fr;
-    b_base[j] = A_BYTES + (R >> 3) * GROUP_BYTES + (R & 7) * 128;
+    b_base[j] = (GA + (R >> 3)) * GROUP_BYTES + (R & 7) * 128;
   }
 #pragma unroll
   for (int kk = 0; kk < BK / 16; ++kk) koff[kk] = ((kk * 2 + fh) ^ (fr & 7)) << 4;
-  float ss[TM];                                         // sum of x^2 of this lane's fragment elements
-#pragma unroll
-  for (int i = 0; i < TM; ++i) ss[i] = 0.f;
 
   // Fragment reads run one K-step ahead of the MFMAs that consume them, so the
   // LDS latency is covered by a full K-step of matrix work.
   struct Frags { f16x8 a[TM], b[TN]; };
   auto read_frags = [&](Frags& f, const char* base, int kk) {
-    if (ASRC) {
-      const int q0 = (kk * 2 + fh) * 2;                 // first of the two 4-float chunks of this K-step
-      const f16x8 g8 = *reinterpret_cast<const f16x8*>(base + A_BYTES + GB * GROUP_BYTES + wave * 128 +
-                                                       (kk * 2 + fh) * 16);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const f32x4 x0 = *reinterpret_cast<const f32x4*>(base + a_base[i] + ((q0 ^ a_x[i]) << 4));
-        const f32x4 x1 = *reinterpret_cast<const f32x4*>(base + a_base[i] + (((q0 + 1) ^ a_x[i]) << 4));
-        if (MODE == GEMM_SWIGLU_F16)
-          ss[i] += x0[0] * x0[0] + x0[1] * x0[1] + x0[2] * x0[2] + x0[3] * x0[3] + x1[0] * x1[0] +
-                   x1[1] * x1[1] + x1[2] * x1[2] + x1[3] * x1[3];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          f.a[i][e] = f2h_sat(x0[e] * h2f(g8[e]));
-          f.a[i][4 + e] = f2h_sat(x1[e] * h2f(g8[4 + e]));
-        }
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < TM; ++i) f.a[i] = *reinterpret_cast<const f16x8*>(base + a_base[i] + koff[kk]);
-    }
+    for (int i = 0; i < TM; ++i) f.a[i] = *reinterpret_cast<const f16x8*>(base + a_base[i] + koff[kk]);
 #pragma unroll
     for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const f16x8*>(base + b_base[j] + koff[kk]);
   };
@@ -439,20 +383,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
       }
     }
   }
-  // (all remaining in-flight loads target LDS only; the epilogue does not touch the ring)
+  // (all remaining in-flight loads target LDS only; the epilogue does not touch LDS)
 
   if (MODE == GEMM_SWIGLU_F16) {
     f16* C = reinterpret_cast<f16*>(Cv);
-    if (ASRC) {
-      // row sums of squares: lanes fr and fr + 32 hold the two K halves of row fr; the waves
-      // of one row tile all hold the same sums
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const float t = ss[i] + __shfl_xor(ss[i], 32);
-        if (fh == 0) row_ss[wm * (BM / WM) + i * 32 + fr] = t;
-      }
-      __syncthreads();
-    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -460,16 +394,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
         const int f = tile_n * (BN / 2) + (wn * (BN / WN) + j * 32) / 2 + fr;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int rt = wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
-          const int m = m0 + rt;
-          float gte = acc[i][j][v], up = acc[i][j + 1][v];
-          if (ASRC) {
-            const float r = 1.0f / sqrtf(row_ss[rt] / (float)K + X.eps);
-            gte *= r;
-            up *= r;
-          }
+          const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
           if (m < M && f < N)
-            C[(int64_t)m * ldc + f] = f2h_sat(silu_f(gte) * up);
+            C[(int64_t)m * ldc + f] = f2h_sat(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
         }
       }
   } else {
@@ -495,9 +422,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
   wait_vmcnt(0);
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int MODE, int ASRC = 0>
+template <int BM, int BN, int WM, int WN, int STAGES, int MODE>
 hipError_t run_dma(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
-                   int splits, GemmX X = GemmX{nullptr, nullptr, 0.f, nullptr, 0}) {
+                   int splits) {
   if (K % BK) return hipErrorInvalidValue;
   constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_F16 ? BN / 2 : BN;
   const int n_tiles = (N + n_out_per_tile - 1) / n_out_per_tile, m_tiles = (M + BM - 1) / BM;
@@ -506,8 +433,8 @@ hipError_t run_dma(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, 
   const int sps = (nk + splits - 1) / splits;
   splits = (nk + sps - 1) / sps;
   const int grid = grid_blocks(m_tiles, n_tiles, splits);
-  gemm_dma_kernel<BM, BN, WM, WN, STAGES, MODE, ASRC><<<grid, WM * WN * 64, 0, s>>>(
-      A, X, W, C, M, N, K, ldc, m_tiles, n_tiles, sps, (splits > 1 || MODE == GEMM_ADD_F32) ? 1 : 0);
+  gemm_dma_kernel<BM, BN, WM, WN, STAGES, MODE><<<grid, WM * WN * 64, 0, s>>>(
+      A, W, C, M, N, K, ldc, m_tiles, n_tiles, sps, (splits > 1 || MODE == GEMM_ADD_F32) ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -532,8 +459,7 @@ hipError_t run(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, int 
 
 template <int MODE>
 hipError_t dispatch(hipStream_t s, int cfg, const f16* A, const GemmW& W, void* C, int M, int N, int K,
-                    int ldc, int splits, GemmX X) {
-  if (X.zero && cfg < 7) return hipErrorInvalidValue;   // only the direct-to-LDS kernels clear a buffer
+                    int ldc, int splits) {
   switch (cfg) {
     case 0: return run<128, 128, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 1: return run<256, 128, 4, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
@@ -543,49 +469,27 @@ hipError_t dispatch(hipStream_t s, int cfg, const f16* A, const GemmW& W, void* 
     case 5: return run<128, 64, 2, 1, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 6: return run<64, 64, 1, 1, MODE>(s, A, W, C, M, N, K, ldc, splits);
     // direct-to-LDS ring (K % 64 == 0)
-    case 7: return run_dma<128, 128, 2, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 8: return run_dma<128, 128, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 9: return run_dma<256, 128, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 10: return run_dma<64, 128, 1, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 11: return run_dma<64, 128, 1, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 12: return run_dma<32, 128, 1, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 13: return run_dma<128, 64, 2, 1, 4, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 14: return run_dma<256, 64, 4, 1, 3, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 15: return run_dma<128, 128, 2, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 16: return run_dma<256, 256, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 17: return run_dma<256, 128, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 18: return run_dma<256, 256, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 19: return run_dma<256, 256, 2, 4, 2, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 20: return run_dma<128, 128, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
-    case 21: return run_dma<128, 128, 4, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
+    case 7: return run_dma<128, 128, 2, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 8: return run_dma<128, 128, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 9: return run_dma<256, 128, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 10: return run_dma<64, 128, 1, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 11: return run_dma<64, 128, 1, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 12: return run_dma<32, 128, 1, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 13: return run_dma<128, 64, 2, 1, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 14: return run_dma<256, 64, 4, 1, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 15: return run_dma<128, 128, 2, 2, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 16: return run_dma<256, 256, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 17: return run_dma<256, 128, 2, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 18: return run_dma<256, 256, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 19: return run_dma<256, 256, 2, 4, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 20: return run_dma<128, 128, 4, 2, 2, MODE>(s, A, W, C, M, N, K, ldc, splits);
+    case 21: return run_dma<128, 128, 4, 2, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
     case 22:   // one 32-column panel per wave: no room for a gate/up pair
-      if constexpr (MODE != GEMM_SWIGLU_F16) return run_dma<32, 128, 1, 4, 4, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
+      if constexpr (MODE != GEMM_SWIGLU_F16) return run_dma<32, 128, 1, 4, 4, MODE>(s, A, W, C, M, N, K, ldc, splits);
       else return hipErrorInvalidValue;
     case 23:
-      if constexpr (MODE != GEMM_SWIGLU_F16) return run_dma<64, 128, 2, 4, 3, MODE>(s, A, W, C, M, N, K, ldc, splits, X);
+      if constexpr (MODE != GEMM_SWIGLU_F16) return run_dma<64, 128, 2, 4, 3, MODE>(s, A, W, C, M, N, K, ldc, splits);
       else return hipErrorInvalidValue;
-    default: return hipErrorInvalidValue;
-  }
-}
-
-// Configurations of the fused-norm input (float32 rows, ASRC = 1): decode-size products only.
-template <int MODE>
-hipError_t dispatch_x(hipStream_t s, int cfg, const GemmX& X, const GemmW& W, void* C, int M, int N, int K,
-                      int ldc, int splits) {
-  switch (cfg) {
-    case 0: return run_dma<32, 128, 1, 2, 4, MODE, 1>(s, nullptr, W, C, M, N, K, ldc, splits, X);
-    case 1:
-      if constexpr (MODE != GEMM_SWIGLU_F16) return run_dma<32, 128, 1, 4, 4, MODE, 1>(s, nullptr, W, C, M, N, K, ldc, splits, X);
-      else return hipErrorInvalidValue;
-    case 2: return run_dma<64, 128, 1, 2, 3, MODE, 1>(s, nullptr, W, C, M, N, K, ldc, splits, X);
-    case 3:
-      if constexpr (MODE != GEMM_SWIGLU_F16) return run_dma<64, 128, 2, 4, 3, MODE, 1>(s, nullptr, W, C, M, N, K, ldc, splits, X);
-      else return hipErrorInvalidValue;
-    case 4: return run_dma<128, 128, 4, 2, 2, MODE, 1>(s, nullptr, W, C, M, N, K, ldc, splits, X);
-    case 5: return run_dma<128, 128, 4, 2, 3, MODE, 1>(s, nullptr, W, C, M, N, K, ldc, splits, X);
-    case 6: return run_dma<32, 64, 1, 1, 4, MODE, 1>(s, nullptr, W, C, M, N, K, ldc, splits, X);
-    case 7: return run_dma<64, 64, 1, 1, 4, MODE, 1>(s, nullptr, W, C, M, N, K, ldc, splits, X);
-    case 8: return run_dma<32, 128, 1, 2, 3, MODE, 1>(s, nullptr, W, C, M, N, K, ldc, splits, X);
     default: return hipErrorInvalidValue;
   }
 }
@@ -593,7 +497,6 @@ hipError_t dispatch_x(hipStream_t s, int cfg, const GemmX& X, const GemmW& W, vo
 }  // namespace
 
 int gemm_num_configs() { return 24; }
-int gemm_x_num_configs() { return 9; }
 
 // Tile configuration and K split for a product of this shape: rules read off
 // sweeps over every configuration on the MI355X at the decoder's shapes
@@ -692,81 +595,29 @@ void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
   *splits = sp;
 }
 
-static bool segments_ok(const GemmW& W, int N) {
-  return !(W.end[0] > N || (W.end[0] < N && (!W.ptr[1] || W.end[1] > N)) ||
-           (W.end[0] < N && W.end[1] < N && (!W.ptr[2] || W.end[2] != N)));
-}
-
 hipError_t launch_gemm_cfg(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,
-                           GemmMode mode, int cfg, int splits, float* zero, int zero_n) {
+                           GemmMode mode, int cfg, int splits) {
   if (M <= 0 || N <= 0 || K <= 0 || K % 8 || ldc < N || !A || !C || !W.ptr[0]) return hipErrorInvalidValue;
   if (((uintptr_t)A | (uintptr_t)W.ptr[0] | (uintptr_t)W.ptr[1] | (uintptr_t)W.ptr[2]) & 15)
     return hipErrorInvalidValue;
-  if (zero && (zero_n <= 0 || zero_n % 4 || ((uintptr_t)zero & 15))) return hipErrorInvalidValue;
   int c0, s0;
   gemm_choose(M, N, K, mode, &c0, &s0);
   if (cfg < 0) cfg = c0;
   if (splits < 0) splits = s0;
-  const GemmX X{nullptr, nullptr, 0.f, zero, zero ? zero_n : 0};
   switch (mode) {
     case GEMM_STORE_F32:
-      if (!segments_ok(W, N)) return hipErrorInvalidValue;
-      return dispatch<GEMM_STORE_F32>(s, cfg, A, W, C, M, N, K, ldc, splits, X);
+      if (W.end[0] > N || (W.end[0] < N && (!W.ptr[1] || W.end[1] > N)) ||
+          (W.end[0] < N && W.end[1] < N && (!W.ptr[2] || W.end[2] != N)))
+        return hipErrorInvalidValue;
+      return dispatch<GEMM_STORE_F32>(s, cfg, A, W, C, M, N, K, ldc, splits);
     case GEMM_ADD_F32:
       if (W.end[0] != N) return hipErrorInvalidValue;
-      return dispatch<GEMM_ADD_F32>(s, cfg, A, W, C, M, N, K, ldc, splits, X);
+      return dispatch<GEMM_ADD_F32>(s, cfg, A, W, C, M, N, K, ldc, splits);
     case GEMM_SWIGLU_F16:
       if (!W.ptr[1]) return hipErrorInvalidValue;
-      return dispatch<GEMM_SWIGLU_F16>(s, cfg, A, W, C, M, N, K, ldc, 1, X);
+      return dispatch<GEMM_SWIGLU_F16>(s, cfg, A, W, C, M, N, K, ldc, 1);
   }
   return hipErrorInvalidValue;
-}
-
-bool gemm_zero_ok(int M, int N, int K, GemmMode mode) {
-  int c, sp;
-  gemm_choose(M, N, K, mode, &c, &sp);
-  return c >= 7;
-}
-
-// Fused-norm input: tile configuration and K split.  QKV-like products (store) split K so that
-// the grid holds about one work-group per compute unit; gate/up walks the whole row (its
-// epilogue needs the row's sum of squares) and is not split.
-void gemm_x_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits) {
-  const int nk = K / BK;
-  if (mode == GEMM_SWIGLU_F16) {
-    *splits = 1;
-    *cfg = M <= 32 ? 0 : (M <= 64 ? 2 : (M <= 128 ? 5 : 4));
-    return;
-  }
-  const int n_tiles = (N + 127) / 128;
-  int bm;
-  if (M <= 32) { *cfg = 1; bm = 32; }
-  else if (M <= 64) { *cfg = 3; bm = 64; }
-  else { *cfg = 5; bm = 128; }
-  *splits = split_for(M, bm, n_tiles, nk);
-}
-
-bool gemm_x_ok(int K) { return K % BK == 0; }
-
-hipError_t launch_gemm_x(hipStream_t s, GemmX X, GemmW W, void* C, int M, int N, int K, int ldc,
-                         GemmMode mode, int cfg, int splits) {
-  if (M <= 0 || N <= 0 || K <= 0 || K % BK || ldc < N || !X.x || !X.gain || !C || !W.ptr[0] ||
-      mode == GEMM_ADD_F32 || !(X.eps >= 0.f))
-    return hipErrorInvalidValue;
-  if (((uintptr_t)X.x | (uintptr_t)X.gain | (uintptr_t)W.ptr[0] | (uintptr_t)W.ptr[1] | (uintptr_t)W.ptr[2]) & 15)
-    return hipErrorInvalidValue;
-  if (X.zero && (X.zero_n <= 0 || X.zero_n % 4 || ((uintptr_t)X.zero & 15))) return hipErrorInvalidValue;
-  if (!X.zero) X.zero_n = 0;
-  int c0, s0;
-  gemm_x_choose(M, N, K, mode, &c0, &s0);
-  if (cfg < 0) cfg = c0;
-  if (splits < 0) splits = s0;
-  if (mode == GEMM_STORE_F32) {
-    if (!segments_ok(W, N)) return hipErrorInvalidValue;
-    return dispatch_x<GEMM_STORE_F32>(s, cfg, X, W, C, M, N, K, ldc, splits);
-  }
-  if (!W.ptr[1]) return hipErrorInvalidValue;
-  return dispatch_x<GEMM_SWIGLU_F16>(s, cfg, X, W, C, M, N, K, ldc, 1);
 }
 
 hipError_t launch_gemm(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,

@@ -18,10 +18,8 @@ struct SeqState {              // device-resident per-sequence state
   int max_seq_len, max_blocks;
 };
 
-// zero_out (optional): float32 [M, zero_cols] cleared row by row alongside.
 hipError_t launch_embed(hipStream_t s, const f16* embed, int hidden, int vocab, int M, RowMeta rm,
-                        const int32_t* tokens_in, const int32_t* new_block, SeqState st, float* h,
-                        float* zero_out = nullptr, int zero_cols = 0);
+                        const int32_t* tokens_in, const int32_t* new_block, SeqState st, float* h);
 // zero_out (optional): float32 [M, zero_cols] cleared row by row alongside (the
 // buffer a following split-K product accumulates into).
 hipError_t launch_rmsnorm(hipStream_t s, const float* x, const f16* gain, f16* y, int M, int hidden,
@@ -57,33 +55,11 @@ hipError_t launch_gemm(hipStream_t s, const f16* A, GemmW W, void* C, int M, int
                        GemmMode mode);
 // Same with an explicit tile configuration (0 .. gemm_num_configs()-1) and K
 // split; -1 = take the tuned choice.  A split > 1 accumulates with float32
-// atomics: for GEMM_STORE_F32 the caller must have zeroed C.  `zero` (optional, only where
-// gemm_zero_ok says so): a float32 buffer of zero_n elements (multiple of 4) that the launch
-// clears alongside, e.g. the accumulator of a later split-K product.
+// atomics: for GEMM_STORE_F32 the caller must have zeroed C.
 hipError_t launch_gemm_cfg(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,
-                           GemmMode mode, int cfg, int splits, float* zero = nullptr, int zero_n = 0);
+                           GemmMode mode, int cfg, int splits);
 void gemm_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits);
-bool gemm_zero_ok(int M, int N, int K, GemmMode mode);
 int gemm_num_configs();
-
-// The same product with RMSNorm taken apart (decode-size row counts): the A operand is
-// half(x * gain) of float32 rows x, converted inside the kernel; the row factor
-// r = 1/sqrt(mean x^2 + eps) is a scalar per output row and is applied after the product.
-//   GEMM_SWIGLU_F16: C = silu(r A gate^T) * (r A up^T), r computed by the kernel (K is not split);
-//   GEMM_STORE_F32:  C = A W^T WITHOUT r: the consumer multiplies its row by r.
-// K % 64 == 0 (gemm_x_ok).  cfg 0 .. gemm_x_num_configs()-1 or -1, splits as above.
-struct GemmX {
-  const float* x;      // [M, K] float32 rows
-  const f16* gain;     // [K]
-  float eps;
-  float* zero;         // optional: float32 buffer of zero_n elements (multiple of 4) cleared by
-  int zero_n;          // the launch (the accumulator of a later split-K product)
-};
-hipError_t launch_gemm_x(hipStream_t s, GemmX X, GemmW W, void* C, int M, int N, int K, int ldc,
-                         GemmMode mode, int cfg, int splits);
-void gemm_x_choose(int M, int N, int K, GemmMode mode, int* cfg, int* splits);
-bool gemm_x_ok(int K);
-int gemm_x_num_configs();
 
 // ---- attention.hip ----------------------------------------------------------
 struct AttnWork {              // prefill work item: a tile of consecutive query rows of one sequence
@@ -95,15 +71,11 @@ int attn_prefill_tile_rows(int n_q_heads, int n_kv_heads);   // 16 or 32
 // token's k happen inside, and the appended k, v are stored into the sequence's block
 // (table entry pos/16 must be installed).  Context = positions 0 .. pos.  `chunk` tokens per
 // split (multiple of 128, at most 2048); with n_splits > 1 the partials go to
-// `part_o` / `part_ml` and launch_attn_merge combines them into `out`.  With `xres`
-// (float32 [M, hidden], the residual rows the QKV rows were projected from WITHOUT their
-// RMSNorm row factor, see launch_gemm_x) q, k and v are first multiplied by
-// 1/sqrt(mean xres[i]^2 + eps).
+// `part_o` / `part_ml` and launch_attn_merge combines them into `out`.
 hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
                               const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                               const float* sin_tab, f16* arena_layer, KvGeom geom, int n_q_heads,
-                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out,
-                              const float* xres = nullptr, int hidden = 0, float eps = 0.f);
+                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out);
 hipError_t launch_attn_merge(hipStream_t s, int M, RowMeta rm, int head_dim, int n_q_heads, int chunk,
                              int n_splits, const float* part_o, const float* part_ml, f16* out);
 hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work, int n_work,

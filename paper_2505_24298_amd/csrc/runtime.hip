@@ -132,7 +132,6 @@ struct areal_ctx {
   std::string err;
   int split_target = 3072;              // decode attention: work-groups per launch aimed at
   int min_chunk = 256;
-  int fuse_norm_rows = 128;             // decode passes of at most this many rows run without RMSNorm kernels
   // measurement hook
   int prof_class = -1, prof_layer = 0, prof_every = 1;
   int64_t prof_pass = 0;
@@ -322,59 +321,12 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
 
   const bool sampled = c->prof_class >= 0 && (c->prof_pass++ % c->prof_every) == 0;
   const double rows = a.M;
-  // Decode passes of few rows run without RMSNorm kernels: the QKV and gate/up products take
-  // the float32 residual rows themselves (times the gain, rounded to half inside the kernel) and
-  // the row factor 1/sqrt(mean x^2 + eps) is applied after the product, by the attention kernel
-  // (q, k, v are linear in it) and by the gate/up epilogue.  The QKV accumulator of the next
-  // layer is cleared by the output projection (by the embedding kernel for layer 0).
-  const int n_qkv = qd + 2 * kd;
-  const bool fused = a.decode && a.M <= c->fuse_norm_rows && gemm_x_ok(H) &&
-                     gemm_zero_ok(a.M, H, qd, GEMM_ADD_F32);
   {
     ProfScope ps(c, AREAL_K_EMBED, -1, sampled, rows);
-    HIP_TRY(c, launch_embed(s, w.embed, H, g.vocab, a.M, a.rm, a.tokens_in, a.new_block, st, h,
-                            fused ? qkv : nullptr, n_qkv));
+    HIP_TRY(c, launch_embed(s, w.embed, H, g.vocab, a.M, a.rm, a.tokens_in, a.new_block, st, h));
   }
   for (int l = 0; l < g.n_layers; ++l) {
     f16* arena_l = arena + (int64_t)l * c->geom.layer_stride;
-    if (fused) {
-      const f16 *bq = w.has_bias ? w.bq[l] : nullptr, *bk = w.has_bias ? w.bk[l] : nullptr,
-                *bv = w.has_bias ? w.bv[l] : nullptr;
-      {
-        ProfScope ps(c, AREAL_K_GEMM_QKV, l, sampled, rows);
-        GemmW wqkv{{w.wq[l], w.wk[l], w.wv[l]}, {qd, qd + kd, qd + 2 * kd}};
-        HIP_TRY(c, launch_gemm_x(s, GemmX{h, w.norm_attn[l], g.rms_eps, nullptr, 0}, wqkv, qkv, a.M, n_qkv, H,
-                                 n_qkv, GEMM_STORE_F32, -1, -1));
-      }
-      {
-        ProfScope ps(c, AREAL_K_ATTN_DECODE, l, sampled, a.attn_units);
-        HIP_TRY(c, launch_attn_decode(s, qkv, a.M, a.rm, st, bq, bk, bv, cos_t, sin_t, arena_l, c->geom, nq,
-                                      a.chunk, a.n_splits, c->wsp<float>(c->lay.part_o),
-                                      c->wsp<float>(c->lay.part_ml), attn, h, H, g.rms_eps));
-      }
-      if (a.n_splits > 1) {
-        ProfScope ps(c, AREAL_K_ATTN_MERGE, l, sampled, rows);
-        HIP_TRY(c, launch_attn_merge(s, a.M, a.rm, d, nq, a.chunk, a.n_splits, c->wsp<float>(c->lay.part_o),
-                                     c->wsp<float>(c->lay.part_ml), attn));
-      }
-      {
-        ProfScope ps(c, AREAL_K_GEMM_O, l, sampled, rows);
-        GemmW wo{{w.wo[l], nullptr, nullptr}, {H, 0, 0}};
-        HIP_TRY(c, launch_gemm_cfg(s, attn, wo, h, a.M, H, qd, H, GEMM_ADD_F32, -1, -1, qkv, a.M * n_qkv));
-      }
-      {
-        ProfScope ps(c, AREAL_K_GEMM_GATEUP, l, sampled, rows);
-        GemmW wgu{{w.wgate[l], w.wup[l], nullptr}, {F, 0, 0}};
-        HIP_TRY(c, launch_gemm_x(s, GemmX{h, w.norm_ffn[l], g.rms_eps, nullptr, 0}, wgu, act, a.M, F, H, F,
-                                 GEMM_SWIGLU_F16, -1, -1));
-      }
-      {
-        ProfScope ps(c, AREAL_K_GEMM_DOWN, l, sampled, rows);
-        GemmW wd{{w.wdown[l], nullptr, nullptr}, {H, 0, 0}};
-        HIP_TRY(c, launch_gemm_cfg(s, act, wd, h, a.M, H, F, H, GEMM_ADD_F32, -1, -1));
-      }
-      continue;
-    }
     {
       ProfScope ps(c, AREAL_K_RMSNORM, l, sampled, rows);
       // the QKV product may split K and accumulate atomically: then its output is cleared here
@@ -601,10 +553,6 @@ int areal_create(const areal_model_cfg* cfg, areal_ctx** out) {
   if (const char* e = getenv("AREAL_DECODE_SPLIT_TARGET")) {   // tuning knob for sweeps
     const int v = atoi(e);
     if (v >= 64 && v <= 65536) c->split_target = v;
-  }
-  if (const char* e = getenv("AREAL_FUSE_NORM_MAX_ROWS")) {
-    const int v = atoi(e);
-    if (v >= 0 && v <= 65536) c->fuse_norm_rows = v;
   }
   if (const char* e = getenv("AREAL_DECODE_MIN_CHUNK")) {
     const int v = atoi(e);
@@ -1121,16 +1069,6 @@ int areal_op_gemm(void* stream, const void* A, const void* W0, const void* W1, v
   if (e == hipErrorInvalidValue) return AREAL_E_INVAL;
   return e == hipSuccess ? AREAL_OK : AREAL_E_HIP;
 }
-int areal_op_gemm_x(void* stream, const void* X, const void* gain, float eps, const void* W0, const void* W1,
-                    void* C, int32_t M, int32_t N, int32_t K, int32_t mode, int32_t cfg, int32_t splits) {
-  if ((mode != 0 && mode != 2) || !X || !gain || !W0 || !C || (mode == 2 && !W1)) return AREAL_E_INVAL;
-  GemmW w{{(const f16*)W0, mode == 2 ? (const f16*)W1 : nullptr, nullptr}, {N, 0, 0}};
-  hipError_t e = launch_gemm_x((hipStream_t)stream, GemmX{(const float*)X, (const f16*)gain, eps, nullptr, 0}, w, C,
-                               M, N, K, N, (GemmMode)mode, cfg, splits);
-  if (e == hipErrorInvalidValue) return AREAL_E_INVAL;
-  return e == hipSuccess ? AREAL_OK : AREAL_E_HIP;
-}
-int areal_op_gemm_x_num_configs(void) { return gemm_x_num_configs(); }
 int areal_op_gemm_num_configs(void) { return gemm_num_configs(); }
 int areal_op_gemm_choose(int32_t M, int32_t N, int32_t K, int32_t mode, int32_t* cfg_out, int32_t* splits_out) {
   if (M <= 0 || N <= 0 || K <= 0 || mode < 0 || mode > 2 || !cfg_out || !splits_out) return AREAL_E_INVAL;

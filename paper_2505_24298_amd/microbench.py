@@ -11,9 +11,6 @@
       shapes (qkv, o, gateup, down, lmhead of the 1.5B shape; qkv7 ... lmhead7 of the 7B shape);
       weights rotate over
       > 1 GB so they come from HBM.
-  python3 paper_2505_24298_amd/microbench.py gemm-x [M,M,...] [shape,...]
-      the same sweep for the products that take float32 rows and apply RMSNorm themselves
-      (qkv, gateup, qkv7, gateup7).
   python3 paper_2505_24298_amd/microbench.py prefill [qwen2-1.5b|qwen2-7b]
       prefill of 32x256, 8x2048, 4x8000 tokens: per-kernel time of one layer.
   python3 paper_2505_24298_amd/microbench.py score
@@ -127,51 +124,6 @@ def gemm(ms_arg, shapes_arg):
         del Ws, W1s
 
 
-def gemm_x(ms_arg, shapes_arg):
-    import torch
-    from paper_2505_24298_amd import binding
-    L = binding.lib()
-    ncfg = L.areal_op_gemm_x_num_configs()
-    shapes = {"qkv": (2048, 1536, 0), "gateup": (8960, 1536, 2), "qkv7": (4608, 3584, 0),
-              "gateup7": (18944, 3584, 2)}
-    Ms = [int(x) for x in ms_arg.split(",")]
-    g = torch.Generator(device="cuda").manual_seed(0)
-    for name in shapes_arg.split(","):
-        N, K, mode = shapes[name]
-        wbytes = N * K * 2 * (2 if mode == 2 else 1)
-        ncopy = max(2, min(64, int(1.2e9 // wbytes)))
-        mk = lambda: (torch.randn((N, K), generator=g, device="cuda") * 0.02).to(torch.float16)
-        Ws = [mk() for _ in range(ncopy)]
-        W1s = [mk() for _ in range(ncopy)] if mode == 2 else None
-        gain = torch.ones(K, device="cuda", dtype=torch.float16)
-        for M in Ms:
-            Xs = [torch.randn((M, K), generator=g, device="cuda") for _ in range(ncopy)]
-            Cs = [torch.zeros((M, N), device="cuda", dtype=torch.float16 if mode == 2 else torch.float32)
-                  for _ in range(ncopy)]
-            for cfg in range(ncfg):
-                for splits in ([1] if mode == 2 else [1, 2, 3, 4, 6, 8, 12]):
-                    iters = 3 * ncopy
-
-                    def run(n):
-                        for i in range(n):
-                            binding.op_gemm_x(Xs[i % ncopy], gain, 1e-6, Ws[i % ncopy],
-                                              None if W1s is None else W1s[i % ncopy], Cs[i % ncopy], mode, cfg, splits)
-                    try:
-                        run(ncopy)
-                    except binding.ArealError:        # configuration does not serve this epilogue
-                        continue
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    run(iters)
-                    e1.record()
-                    torch.cuda.synchronize()
-                    us = e0.elapsed_time(e1) * 1e3 / iters
-                    print(json.dumps(dict(shape=name + "-x", M=M, cfg=cfg, splits=splits, us=round(us, 2),
-                                          weight_GBps=round(wbytes / us / 1e3, 1))), flush=True)
-            del Xs, Cs
-        del Ws, W1s
-
-
 def prefill(shape_name="qwen2-1.5b"):
     import torch
     from paper_2505_24298_amd import binding, synth
@@ -245,8 +197,6 @@ if __name__ == "__main__":
     elif what == "gemm":
         gemm(sys.argv[2] if len(sys.argv) > 2 else "32,64,128,256",
              sys.argv[3] if len(sys.argv) > 3 else "qkv,o,gateup,down,lmhead")
-    elif what == "gemm-x":
-        gemm_x(sys.argv[2] if len(sys.argv) > 2 else "24,48,100", sys.argv[3] if len(sys.argv) > 3 else "qkv,gateup")
     elif what == "prefill":
         prefill(sys.argv[2] if len(sys.argv) > 2 else "qwen2-1.5b")
     elif what == "score":

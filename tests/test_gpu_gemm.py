@@ -48,47 +48,3 @@ def test_gemm_all_configs(M, N, K):
         want = ref0 / (1.0 + np.exp(-ref0)) * ref1
         got = Cb.float().cpu().numpy()
         assert np.abs(got - want).max() <= 2 ** -10 * np.abs(want).max() + 1e-6, cfg
-
-
-@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (24, 2048, 1536), (37, 344, 128), (100, 1000, 1536),
-                                   (130, 520, 3584), (256, 1536, 1536)])
-def test_gemm_fused_norm_input_all_configs(M, N, K):
-    """The product whose A operand is formed inside the kernel from float32 rows times the
-    gain (RMSNorm taken apart): the store mode returns the product without the row factor,
-    the gate/up mode applies the factor itself.  Reference: float64 product of the same
-    half-rounded operand, rows scaled far apart so that a factor taken from the wrong row shows."""
-    import torch
-    from paper_2505_24298_amd import binding
-    L = binding.lib()
-    g = torch.Generator(device="cuda").manual_seed(M * 11 + N)
-    X = torch.randn((M, K), generator=g, device="cuda")
-    X *= torch.logspace(-1.5, 1.5, M, device="cuda")[:, None]           # row scales 0.03 .. 30
-    gain = (1.0 + 0.3 * torch.randn(K, generator=g, device="cuda")).to(torch.float16)
-    W0 = (torch.randn((N, K), generator=g, device="cuda") * 0.05).to(torch.float16)
-    W1 = (torch.randn((N, K), generator=g, device="cuda") * 0.05).to(torch.float16)
-    eps = 1e-6
-    A = (X * gain.float()).to(torch.float16)                           # one rounding, as in the kernel
-    ref0, ref1 = _ref(A, W0), _ref(A, W1)
-    r = 1.0 / np.sqrt((X.double().cpu().numpy() ** 2).mean(axis=1, keepdims=True) + eps)
-    row_scale = np.abs(ref0).max(axis=1, keepdims=True) + 1e-30
-    for cfg in list(range(L.areal_op_gemm_x_num_configs())) + [-1]:
-        for splits in (1, 3, -1):
-            C = torch.zeros((M, N), device="cuda")
-            binding.op_gemm_x(X, gain, eps, W0, None, C, 0, cfg, splits)
-            err = np.abs(C.cpu().numpy() - ref0) / row_scale
-            assert err.max() <= 2e-5 * (K ** 0.5), (cfg, splits)
-        Cb = torch.zeros((M, N), device="cuda", dtype=torch.float16)
-        if cfg in (1, 3):          # four waves across 128 columns: no gate/up pair in a wave
-            with pytest.raises(binding.ArealError):
-                binding.op_gemm_x(X, gain, eps, W0, W1, Cb, 2, cfg, 1)
-            continue
-        binding.op_gemm_x(X, gain, eps, W0, W1, Cb, 2, cfg, 1)
-        z0, z1 = ref0 * r, ref1 * r
-        want = z0 / (1.0 + np.exp(-z0)) * z1
-        got = Cb.float().cpu().numpy()
-        assert np.abs(got - want).max() <= 2 ** -10 * np.abs(want).max() + 1e-6, cfg
-    # K off the 64-wide slabs is refused (the caller keeps the separate RMSNorm kernel there)
-    if K % 64 == 0:
-        with pytest.raises(binding.ArealError):
-            binding.op_gemm_x(X[:, :K - 8].contiguous(), gain[:K - 8].contiguous(), eps,
-                              W0[:, :K - 8].contiguous(), None, torch.zeros((M, N), device="cuda"), 0, -1, 1)

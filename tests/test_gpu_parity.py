@@ -106,23 +106,6 @@ def test_tiny_config_teacher_forced(torch, binding):
     assert dl <= LOGIT_TOL and dlb <= LOGP_TOL and dlf <= LOGP_TOL
 
 
-def test_tiny_config_with_separate_rmsnorm_kernels(torch, binding, monkeypatch):
-    """Decode passes of few rows run without RMSNorm kernels by default (the row factor is
-    applied after the QKV and gate/up products); AREAL_FUSE_NORM_MAX_ROWS=0 keeps the
-    separate kernels.  Both must meet the same tolerance; non-unit gains and a QKV bias so
-    that a factor applied on the wrong side of either shows."""
-    cfg, wl, prompts, outs = synth.make_workload("tiny")
-    w = synth.random_gains(synth.make_weights(cfg, 0, qkv_bias=True, std=0.04), 12, spread=0.5)
-    for knob in ("0", "4", None):
-        if knob is None:
-            monkeypatch.delenv("AREAL_FUSE_NORM_MAX_ROWS", raising=False)
-        else:
-            monkeypatch.setenv("AREAL_FUSE_NORM_MAX_ROWS", knob)      # 4: fused for the last rows only
-        dl, dlb, dlf = _teacher_forced_run(torch, binding, cfg, w, prompts[:6], 24, qkv_bias=True)
-        print(f"tiny, fuse rows {knob}: logits {dl:.2e}  logp_behav {dlb:.2e}  logp_full {dlf:.2e}")
-        assert dl <= LOGIT_TOL and dlb <= LOGP_TOL and dlf <= LOGP_TOL
-
-
 def test_tiny_bias_gains_large_values_chunked_prefill(torch, binding):
     """QKV bias, non-unit gains, larger weights (logits of order 1), prompts
     longer than one pass (chunked prefill across sequence boundaries), ids not
