@@ -3,6 +3,8 @@
 // its kernel assumes and returns hipErrorInvalidValue instead of launching
 // when they do not hold.
 #pragma once
+#include <string>
+
 #include "common.hpp"
 
 namespace areal {
@@ -83,9 +85,14 @@ hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work
                                f16* out);
 
 // ---- sampler.hip ------------------------------------------------------------
+// `scratch` (optional, device, 16-byte aligned, sampler_scratch_bytes()): lets the launch spread a
+// row over several work-groups when few rows are sampled with top-p = 1; its contents are
+// overwritten.  Without it every row is one work-group.
 hipError_t launch_sampler(hipStream_t s, int n, int vocab, const float* logits, const int32_t* seq_ids,
                           const int32_t* positions, float inv_temperature, float top_p, uint64_t seed,
-                          const int32_t* forced, int32_t* tokens_out, float* logp_behav, float* logp_full);
+                          const int32_t* forced, int32_t* tokens_out, float* logp_behav, float* logp_full,
+                          void* scratch = nullptr);
+size_t sampler_scratch_bytes();
 
 // ---- scoring.hip ------------------------------------------------------------
 // Row r with target[r] >= 0: out[r + 1] = log softmax(logits[r] * inv_t)[target[r]];

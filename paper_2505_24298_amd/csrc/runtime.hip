@@ -31,7 +31,7 @@ thread_local std::string g_create_error;
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {                     // byte offsets into the workspace
-  uint64_t h, xn, qkv, q, attn, act, xlast, part_o, part_ml, hist, table, cos_t, sin_t, ring, wconv,
+  uint64_t h, xn, qkv, q, attn, act, xlast, part_o, part_ml, hist, table, cos_t, sin_t, ring, samp, wconv,
       total;
   uint64_t ring_bytes, wconv_elems;
   int max_blocks;
@@ -87,6 +87,7 @@ Layout make_layout(const areal_model_cfg& c) {
   const uint64_t per_pass = M * 16 + (M / 16 + 2 * (uint64_t)c.max_seqs + 64) * 16 + (uint64_t)c.max_seqs * 16;
   L.ring_bytes = align_up(std::max<uint64_t>(per_pass * 2, 1u << 20), 4096) * kRingSegs;
   L.ring = take(L.ring_bytes);
+  L.samp = take(sampler_scratch_bytes());
   L.wconv_elems = c.convert_weights ? total_params(c) : 0;
   L.wconv = take(L.wconv_elems * 2);
   L.total = off;
@@ -857,7 +858,7 @@ int areal_sample_logprob(areal_ctx* c, int32_t n, const float* logits, const int
   const bool sampled = c->prof_class == AREAL_K_SAMPLER && (c->prof_pass++ % c->prof_every) == 0;
   ProfScope ps(c, AREAL_K_SAMPLER, -1, sampled, (double)n);
   HIP_TRY(c, launch_sampler(c->stream, n, c->cfg.vocab, logits, d_ids, d_pos, inv_t, top_p, seed, forced,
-                            tokens_out, logp_behav, logp_full));
+                            tokens_out, logp_behav, logp_full, c->ws + c->lay.samp));
   return AREAL_OK;
 }
 

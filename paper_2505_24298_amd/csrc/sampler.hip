@@ -6,19 +6,33 @@
 // 16-byte loads); all order-sensitive steps work on per-segment integer sums
 // in LDS, so the result does not depend on how the row was split.
 //
+// With few rows (fewer than half the compute units) and the whole vocabulary
+// kept (top-p = 1) a row is spread over several work-groups instead: partial
+// maxima, then per-segment masses, go through a scratch buffer in device
+// memory, and a third launch scans the masses and picks the token.  The masses
+// are integers and the maximum is exact, so the token is the same either way.
+//
 // Determinism contract (include/areal.h, areal_sample_logprob): the token id
 // is a pure function of the float32 logits.  Every floating-point step that
 // feeds an integer decision is a single IEEE float32 operation; contraction
 // into fused multiply-add is switched off for this whole file.
+#include <algorithm>
+
 #include "kernels.hpp"
 
 #pragma clang fp contract(off)
 
 namespace areal {
+
+constexpr int SEG = 256, MAX_SEG = 1024;       // ids per segment, segments per row at most
+constexpr int SAMPLER_MAX_PARTS = 16;          // work-groups one row can be spread over
+constexpr int SAMPLER_SPLIT_MAX_ROWS = 128;    // rows the scratch buffer holds
+
 namespace {
 
-constexpr int TPB = 1024, NWAVES = 16, SEG = 256, MAX_SEG = 1024;
+constexpr int TPB = 1024, NWAVES = 16;
 constexpr int NBINS = 257;   // masses are 33-bit (0 .. 2^32); top level bins = c >> 24
+
 
 typedef unsigned long long u64;
 
@@ -163,6 +177,105 @@ __device__ __forceinline__ int find_bin(const u64* hist, u64 need, int lane, u64
   bsel = __shfl(bsel, L);
   above_out = shfl_u64(above, L);
   return bsel;
+}
+
+// The last step of both variants.  segmass[s] = kept mass of segment s (LDS), segtie[s] = ties
+// at the threshold before segment s (top-p < 1 only); draws (or takes the forced token), walks
+// the chosen segment in id order and writes the outputs of `row`.
+__device__ __forceinline__ void choose_token(const Row& R, int row, int nseg, float m, u64 S_total, u64 S_nuc,
+                                             bool all_in, u64 tau, u64 n_take, const u64* segmass,
+                                             const uint32_t* segtie, u64* wave_tot, u64* sh_u64, int* sh_int,
+                                             u64 seed, const int32_t* __restrict__ seq_ids,
+                                             const int32_t* __restrict__ positions,
+                                             const int32_t* __restrict__ forced,
+                                             int32_t* __restrict__ tokens_out, float* __restrict__ logp_behav,
+                                             float* __restrict__ logp_full) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, V = R.V;
+  int tok;
+  u64 base = 0;          // kept mass before the chosen segment (draw path)
+  u64 r = 0;
+  if (forced) {
+    tok = forced[row];
+    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+    if (tid == 0) sh_int[2] = tok / SEG;
+  } else {
+    const u64 Rbits = philox_draw(seed, (uint32_t)seq_ids[row], (uint32_t)positions[row]);
+    r = __umul64hi(Rbits, S_nuc);
+    u64 tot;
+    const u64 mine = tid < nseg ? segmass[tid] : 0;
+    const u64 incl = block_incl_scan_u64(mine, wave_tot, tot);
+    if (tid < nseg && incl > r && incl - mine <= r) { sh_int[2] = tid; sh_u64[1] = incl - mine; }
+    tok = -1;
+  }
+  __syncthreads();
+  const int sseg = sh_int[2];
+  base = sh_u64[1];
+
+  // wave 0 walks the chosen segment in id order
+  if (wave == 0) {
+    float z[4];
+    load_z4(R, sseg * SEG + lane * 4, z);
+    u64 c[4], kept[4];
+    uint32_t tie_lane = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      c[k] = mass_of(z[k], m);
+      if (!all_in && sseg * SEG + lane * 4 + k < V && c[k] == tau) tie_lane += 1;
+    }
+    // ties before this lane's first id
+    uint32_t tie_before = 0;
+    if (!all_in) {
+      const u64 incl = wave_incl_scan_u64(tie_lane, lane);
+      tie_before = segtie[sseg] + (uint32_t)(incl - tie_lane);
+    }
+    u64 lane_sum = 0;
+    bool member[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const bool in = sseg * SEG + lane * 4 + k < V;
+      if (all_in) {
+        member[k] = in;
+      } else if (c[k] > tau) {
+        member[k] = in;
+      } else if (c[k] == tau && in) {
+        member[k] = tie_before < n_take;
+        tie_before += 1;
+      } else {
+        member[k] = false;
+      }
+      kept[k] = member[k] ? c[k] : 0;
+      lane_sum += kept[k];
+    }
+    int k_sel = -1;
+    if (forced) {
+      if ((tok % SEG) / 4 == lane) k_sel = tok & 3;
+    } else {
+      const u64 incl = wave_incl_scan_u64(lane_sum, lane);
+      u64 run = base + incl - lane_sum;
+      if (run <= r && r < run + lane_sum) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          if (k_sel < 0) {
+            run += kept[k];
+            if (run > r) k_sel = k;
+          }
+        }
+      }
+    }
+    if (k_sel >= 0) {
+      const int t = sseg * SEG + lane * 4 + k_sel;
+      u64 ct = 0;
+      float zt = 0.f;
+      bool mem = false;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (k == k_sel) { ct = c[k]; zt = z[k]; mem = member[k]; }
+      tokens_out[row] = t;
+      logp_behav[row] = (mem && ct > 0) ? (float)(log((double)ct) - log((double)S_nuc)) : -INFINITY;
+      if (logp_full)
+        logp_full[row] = (float)((double)(zt - m) - (log((double)S_total) - 32.0 * 0.69314718055994530942));
+    }
+  }
 }
 
 __global__ __launch_bounds__(TPB) void sampler_kernel(
@@ -310,104 +423,119 @@ __global__ __launch_bounds__(TPB) void sampler_kernel(
     }
   }
 
-  // ---- choose the token -----------------------------------------------------------
-  int tok;
-  u64 base = 0;          // kept mass before the chosen segment (draw path)
-  u64 r = 0;
-  if (forced) {
-    tok = forced[row];
-    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
-    if (tid == 0) sh_int[2] = tok / SEG;
-  } else {
-    const u64 Rbits = philox_draw(seed, (uint32_t)seq_ids[row], (uint32_t)positions[row]);
-    r = __umul64hi(Rbits, S_nuc);
-    u64 tot;
-    const u64 mine = tid < nseg ? segmass[tid] : 0;
-    const u64 incl = block_incl_scan_u64(mine, wave_tot, tot);
-    if (tid < nseg && incl > r && incl - mine <= r) { sh_int[2] = tid; sh_u64[1] = incl - mine; }
-    tok = -1;
-  }
-  __syncthreads();
-  const int sseg = sh_int[2];
-  base = sh_u64[1];
+  choose_token(R, row, nseg, m, S_total, S_nuc, all_in, tau, n_take, segmass, segtie, wave_tot, sh_u64, sh_int,
+               seed, seq_ids, positions, forced, tokens_out, logp_behav, logp_full);
+}
 
-  // wave 0 walks the chosen segment in id order
-  if (wave == 0) {
+// ---- a row spread over several work-groups (top-p = 1, few rows) -------------------
+// Work-group (part, row) of 4 waves takes segments part*4 + wave, then every parts*4-th.
+constexpr int SPLIT_TPB = 256, SPLIT_WAVES = 4;
+
+__global__ __launch_bounds__(SPLIT_TPB) void sampler_split_max_kernel(int V, const float* __restrict__ logits,
+                                                                      float inv_t, int parts,
+                                                                      float* __restrict__ pmax) {
+  __shared__ float wmax[SPLIT_WAVES];
+  const int row = blockIdx.y, part = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  Row R;
+  R.lp = logits + (int64_t)row * V;
+  R.V = V;
+  R.vec = (V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
+  R.inv_t = inv_t;
+  const int nseg = (V + SEG - 1) / SEG;
+  float mx = -INFINITY;
+  for (int sg = part * SPLIT_WAVES + wave; sg < nseg; sg += parts * SPLIT_WAVES) {
     float z[4];
-    load_z4(R, sseg * SEG + lane * 4, z);
-    u64 c[4], kept[4];
-    uint32_t tie_lane = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      c[k] = mass_of(z[k], m);
-      if (!all_in && sseg * SEG + lane * 4 + k < V && c[k] == tau) tie_lane += 1;
-    }
-    // ties before this lane's first id
-    uint32_t tie_before = 0;
-    if (!all_in) {
-      const u64 incl = wave_incl_scan_u64(tie_lane, lane);
-      tie_before = segtie[sseg] + (uint32_t)(incl - tie_lane);
-    }
-    u64 lane_sum = 0;
-    bool member[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const bool in = sseg * SEG + lane * 4 + k < V;
-      if (all_in) {
-        member[k] = in;
-      } else if (c[k] > tau) {
-        member[k] = in;
-      } else if (c[k] == tau && in) {
-        member[k] = tie_before < n_take;
-        tie_before += 1;
-      } else {
-        member[k] = false;
-      }
-      kept[k] = member[k] ? c[k] : 0;
-      lane_sum += kept[k];
-    }
-    int k_sel = -1;
-    if (forced) {
-      if ((tok % SEG) / 4 == lane) k_sel = tok & 3;
-    } else {
-      const u64 incl = wave_incl_scan_u64(lane_sum, lane);
-      u64 run = base + incl - lane_sum;
-      if (run <= r && r < run + lane_sum) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          if (k_sel < 0) {
-            run += kept[k];
-            if (run > r) k_sel = k;
-          }
-        }
-      }
-    }
-    if (k_sel >= 0) {
-      const int t = sseg * SEG + lane * 4 + k_sel;
-      u64 ct = 0;
-      float zt = 0.f;
-      bool mem = false;
-#pragma unroll
-      for (int k = 0; k < 4; ++k)
-        if (k == k_sel) { ct = c[k]; zt = z[k]; mem = member[k]; }
-      tokens_out[row] = t;
-      logp_behav[row] = (mem && ct > 0) ? (float)(log((double)ct) - log((double)S_nuc)) : -INFINITY;
-      if (logp_full)
-        logp_full[row] = (float)((double)(zt - m) - (log((double)S_total) - 32.0 * 0.69314718055994530942));
-    }
+    load_z4(R, sg * SEG + lane * 4, z);
+    mx = fmaxf(fmaxf(mx, fmaxf(z[0], z[1])), fmaxf(z[2], z[3]));
   }
+  mx = wave_max(mx);
+  if (lane == 0) wmax[wave] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    pmax[row * SAMPLER_MAX_PARTS + part] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+}
+
+__device__ __forceinline__ float row_max_of_parts(const float* __restrict__ pmax, int row, int parts) {
+  float m = pmax[row * SAMPLER_MAX_PARTS];
+  for (int p = 1; p < parts; ++p) m = fmaxf(m, pmax[row * SAMPLER_MAX_PARTS + p]);
+  return m;
+}
+
+__global__ __launch_bounds__(SPLIT_TPB) void sampler_split_mass_kernel(int V, const float* __restrict__ logits,
+                                                                       float inv_t, int parts,
+                                                                       const float* __restrict__ pmax,
+                                                                       u64* __restrict__ segmass_g) {
+  const int row = blockIdx.y, part = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  Row R;
+  R.lp = logits + (int64_t)row * V;
+  R.V = V;
+  R.vec = (V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
+  R.inv_t = inv_t;
+  const int nseg = (V + SEG - 1) / SEG;
+  const float m = row_max_of_parts(pmax, row, parts);
+  for (int sg = part * SPLIT_WAVES + wave; sg < nseg; sg += parts * SPLIT_WAVES) {
+    float z[4];
+    load_z4(R, sg * SEG + lane * 4, z);
+    u64 c = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c += mass_of(z[k], m);
+    c = wave_sum_u64(c);
+    if (lane == 0) segmass_g[(int64_t)row * MAX_SEG + sg] = c;
+  }
+}
+
+__global__ __launch_bounds__(TPB) void sampler_split_pick_kernel(
+    int V, const float* __restrict__ logits, const int32_t* __restrict__ seq_ids,
+    const int32_t* __restrict__ positions, float inv_t, u64 seed, const int32_t* __restrict__ forced, int parts,
+    const float* __restrict__ pmax, const u64* __restrict__ segmass_g, int32_t* __restrict__ tokens_out,
+    float* __restrict__ logp_behav, float* __restrict__ logp_full) {
+  __shared__ u64 segmass[MAX_SEG];
+  __shared__ u64 wave_tot[NWAVES];
+  __shared__ u64 sh_u64[4];
+  __shared__ int sh_int[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  Row R;
+  R.lp = logits + (int64_t)row * V;
+  R.V = V;
+  R.vec = (V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
+  R.inv_t = inv_t;
+  const int nseg = (V + SEG - 1) / SEG;
+  const float m = row_max_of_parts(pmax, row, parts);
+  const u64 mine = tid < nseg ? segmass_g[(int64_t)row * MAX_SEG + tid] : 0;
+  segmass[tid] = mine;
+  u64 S_total;
+  block_incl_scan_u64(mine, wave_tot, S_total);        // its barriers also publish segmass
+  choose_token(R, row, nseg, m, S_total, S_total, true, 0, 0, segmass, nullptr, wave_tot, sh_u64, sh_int, seed,
+               seq_ids, positions, forced, tokens_out, logp_behav, logp_full);
 }
 
 }  // namespace
 
+size_t sampler_scratch_bytes() { return SAMPLER_SPLIT_MAX_ROWS * (SAMPLER_MAX_PARTS * 4 + (size_t)MAX_SEG * 8); }
+
 hipError_t launch_sampler(hipStream_t s, int n, int vocab, const float* logits, const int32_t* seq_ids,
                           const int32_t* positions, float inv_temperature, float top_p, uint64_t seed,
                           const int32_t* forced, int32_t* tokens_out, float* logp_behav,
-                          float* logp_full) {
+                          float* logp_full, void* scratch) {
   if (n <= 0 || vocab <= 0 || (vocab + SEG - 1) / SEG > MAX_SEG || !logits || !tokens_out ||
       !logp_behav || !(inv_temperature > 0.f) || !(top_p > 0.f))
     return hipErrorInvalidValue;
   if (!forced && (!seq_ids || !positions)) return hipErrorInvalidValue;
+  // few rows, whole vocabulary kept: 2 .. 16 work-groups per row, about one per compute unit
+  const int nseg = (vocab + SEG - 1) / SEG;
+  int parts = std::min(SAMPLER_MAX_PARTS, 256 / n);
+  parts = std::min(parts, (nseg + SPLIT_WAVES - 1) / SPLIT_WAVES);
+  if (scratch && top_p >= 1.0f && n <= SAMPLER_SPLIT_MAX_ROWS && parts >= 2) {
+    if ((uintptr_t)scratch & 15) return hipErrorInvalidValue;
+    u64* segmass_g = reinterpret_cast<u64*>(scratch);
+    float* pmax = reinterpret_cast<float*>(segmass_g + (size_t)SAMPLER_SPLIT_MAX_ROWS * MAX_SEG);
+    const dim3 grid(parts, n);
+    sampler_split_max_kernel<<<grid, SPLIT_TPB, 0, s>>>(vocab, logits, inv_temperature, parts, pmax);
+    sampler_split_mass_kernel<<<grid, SPLIT_TPB, 0, s>>>(vocab, logits, inv_temperature, parts, pmax, segmass_g);
+    sampler_split_pick_kernel<<<n, TPB, 0, s>>>(vocab, logits, seq_ids, positions, inv_temperature, (u64)seed,
+                                                forced, parts, pmax, segmass_g, tokens_out, logp_behav, logp_full);
+    return hipGetLastError();
+  }
   sampler_kernel<<<n, TPB, 0, s>>>(vocab, logits, seq_ids, positions, inv_temperature, top_p,
                                    (u64)seed, forced, tokens_out, logp_behav, logp_full);
   return hipGetLastError();

@@ -66,3 +66,30 @@ def test_masses_far_below_the_maximum_are_zero():
         _check(eng, logits, 1.0, top_p, seed=4)
         _check(eng, logits, 1.0, top_p, seed=4, forced=np.array([5, 6, 900, 7]))
     eng.close()
+
+
+@pytest.mark.parametrize("V", [151936, 5000])
+def test_rows_spread_over_work_groups(V):
+    """With few rows and top-p = 1 a row is spread over 2 .. 16 work-groups (partial maxima and
+    segment masses through a scratch buffer); 129 rows and more, and top-p < 1, keep one
+    work-group per row.  Token ids must not depend on the split: 1, 23 and 128 rows (16, 11
+    and 2 work-groups per row at the full vocabulary) against the oracle, and the same rows
+    sampled as part of a batch of 129 (one work-group each) against the rows sampled alone."""
+    import torch
+    rng = np.random.default_rng(V)
+    eng = _engine_for_vocab(V)
+    big = (rng.standard_normal((129, V)) * 0.8).astype(np.float32)
+    big[5] = np.round(big[5] * 3) * 0.25                                   # ties
+    big[7] *= 8.0                                                          # peaked
+    for n in (1, 23, 128):
+        _check(eng, big[:n], 1.0, 1.0, seed=(3 << 32) | 99)
+        forced = rng.integers(0, V, size=n)
+        _check(eng, big[:n], 1.0, 1.0, seed=5, forced=forced)
+    ids = np.arange(129, dtype=np.int32) * 3 + 1
+    pos = (np.arange(129, dtype=np.int32) * 7919) % 30000
+    dl = torch.from_numpy(big).cuda()
+    whole = [t.cpu().numpy() for t in eng.sample_logprob(dl, ids, pos, 1.0, 1.0, 77)]
+    part = [t.cpu().numpy() for t in eng.sample_logprob(dl[:23].contiguous(), ids[:23], pos[:23], 1.0, 1.0, 77)]
+    assert whole[0][:23].tolist() == part[0].tolist()
+    assert np.abs(whole[1][:23] - part[1]).max() < 1e-6 and np.abs(whole[2][:23] - part[2]).max() < 1e-6
+    eng.close()
