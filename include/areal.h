@@ -178,6 +178,28 @@ int areal_sample_logprob(areal_ctx* ctx, int32_t n, const float* logits,
                          const int32_t* forced_tokens,
                          int32_t* tokens_out, float* logp_behav_out, float* logp_full_out);
 
+/* areal_sample_logprob for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  No context: the scratch buffer that lets a row be spread over several
+ * work-groups is a static device array inside the library (about 1 MiB per GPU, held until
+ * the process ends).  The call allocates nothing and takes DEVICE arrays throughout:
+ *   hip_stream  hipStream_t (NULL = default stream) on the current device
+ *   logits      device float32 [n, vocab]
+ *   seq_ids, positions  device int32 [n] (unused, may be NULL, with forced_tokens)
+ *   forced_tokens, tokens_out, logp_behav_out, logp_full_out  as areal_sample_logprob
+ * Same results as areal_sample_logprob (token ids bit for bit).  At most
+ * AREAL_SAMPLE_STATIC_MAX_ROWS rows of at most AREAL_SAMPLE_STATIC_MAX_VOCAB logits per
+ * call; more returns AREAL_E_NOMEM and does nothing (split the batch).  Every call on a
+ * GPU uses that GPU's one array: calls that overlap on one GPU (different streams or
+ * threads) race; calls on one stream are ordered.  Errors: text via areal_last_error(NULL). */
+#define AREAL_SAMPLE_STATIC_MAX_ROWS  128
+#define AREAL_SAMPLE_STATIC_MAX_VOCAB 262144
+int areal_sample_logprob_static(void* hip_stream, int32_t n, int32_t vocab, const float* logits,
+                                const int32_t* seq_ids, const int32_t* positions,
+                                float temperature, float top_p, uint64_t philox_seed,
+                                const int32_t* forced_tokens, int32_t* tokens_out,
+                                float* logp_behav_out, float* logp_full_out);
+
 /* Section 4.1 `update_weights`: interrupt all generations in flight, switch to
  * the new parameters, discard the K/V computed with the old ones and recompute
  * them: every live sequence's whole prefix (prompt + tokens generated so far)

@@ -65,6 +65,9 @@ _SIGNATURES = {
     "areal_sample_logprob": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, _I32P, _I32P, C.c_float,
                                        C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p]),
+    "areal_sample_logprob_static": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p]),
     "areal_update_weights_interrupt": (C.c_int, [C.c_void_p, C.POINTER(Weights), C.c_uint64, _I32P,
                                                  _I32P, C.c_void_p, _I64P]),
     "areal_gate_create": (C.c_void_p, [C.c_int64, C.c_int64]),
@@ -353,6 +356,28 @@ class Areal:
         t, f = C.c_int64(), C.c_int64()
         self._check(self.L.areal_kv_blocks(self.ctx, C.byref(t), C.byref(f)))
         return t.value, f.value
+
+
+def sample_logprob_static(logits, seq_ids, positions, temperature=1.0, top_p=1.0, seed=0, forced_tokens=None,
+                          out=None):
+    """areal_sample_logprob_static on torch device tensors (current stream); allocates only
+    the outputs, and not even those when `out` is given."""
+    import torch
+    n, vocab = logits.shape
+    assert logits.is_cuda and logits.dtype == torch.float32 and logits.is_contiguous()
+    for t in (seq_ids, positions, forced_tokens):
+        assert t is None or (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous())
+    if out is None:
+        out = (torch.empty(n, dtype=torch.int32, device=logits.device),
+               torch.empty(n, dtype=torch.float32, device=logits.device),
+               torch.empty(n, dtype=torch.float32, device=logits.device))
+    p = lambda t: None if t is None else t.data_ptr()
+    rc = lib().areal_sample_logprob_static(torch.cuda.current_stream().cuda_stream, n, vocab, logits.data_ptr(),
+                                           p(seq_ids), p(positions), float(temperature), float(top_p), int(seed),
+                                           p(forced_tokens), out[0].data_ptr(), out[1].data_ptr(), out[2].data_ptr())
+    if rc != OK:
+        raise ArealError(rc, lib().areal_last_error(None).decode())
+    return out
 
 
 def op_gemm(A, W0, W1, C_out, mode, cfg=-1, splits=-1):

@@ -93,6 +93,8 @@ hipError_t launch_sampler(hipStream_t s, int n, int vocab, const float* logits, 
                           const int32_t* forced, int32_t* tokens_out, float* logp_behav, float* logp_full,
                           void* scratch = nullptr);
 size_t sampler_scratch_bytes();
+// text areal_last_error(NULL) returns (calls that have no context)
+void set_global_error(const std::string& msg);
 
 // ---- scoring.hip ------------------------------------------------------------
 // Row r with target[r] >= 0: out[r + 1] = log softmax(logits[r] * inv_t)[target[r]];

@@ -111,6 +111,10 @@ struct WeightSet {
 
 }  // namespace
 
+namespace areal {
+void set_global_error(const std::string& msg) { g_create_error = msg; }
+}  // namespace areal
+
 struct areal_ctx {
   areal_model_cfg cfg;
   Layout lay;

@@ -17,7 +17,10 @@
 // feeds an integer decision is a single IEEE float32 operation; contraction
 // into fused multiply-add is switched off for this whole file.
 #include <algorithm>
+#include <mutex>
+#include <string>
 
+#include "../../include/areal.h"
 #include "kernels.hpp"
 
 #pragma clang fp contract(off)
@@ -26,7 +29,8 @@ namespace areal {
 
 constexpr int SEG = 256, MAX_SEG = 1024;       // ids per segment, segments per row at most
 constexpr int SAMPLER_MAX_PARTS = 16;          // work-groups one row can be spread over
-constexpr int SAMPLER_SPLIT_MAX_ROWS = 128;    // rows the scratch buffer holds
+constexpr int SAMPLER_SPLIT_MAX_ROWS = AREAL_SAMPLE_STATIC_MAX_ROWS;   // rows the scratch buffer holds
+static_assert(AREAL_SAMPLE_STATIC_MAX_VOCAB == SEG * MAX_SEG, "header limit = segments x ids per segment");
 
 namespace {
 
@@ -542,3 +546,77 @@ hipError_t launch_sampler(hipStream_t s, int n, int vocab, const float* logits, 
 }
 
 }  // namespace areal
+
+// ---- the entry point that allocates nothing -----------------------------------------
+// Same sampler, for callers that cannot allocate or hand over a workspace: the scratch
+// buffer of the spread variant is a file-scope device array.  Each GPU the library runs on
+// holds its own copy (about 1 MiB) at its own address until the process ends; the address is
+// looked up once per device, with that device current, and only that pointer (never the
+// array's name, which in host code is a stand-in, not a device address) is handed to kernels.
+namespace {
+
+static __device__ __align__(256) unsigned char g_sampler_scratch[areal::SAMPLER_SPLIT_MAX_ROWS *
+                                                                (areal::SAMPLER_MAX_PARTS * 4 +
+                                                                 (size_t)areal::MAX_SEG * 8)];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's copy of the array (null + message on failure).
+void* static_scratch(std::string* why) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    *why = std::string("hipGetDevice: ") + (e != hipSuccess ? hipGetErrorString(e) : "device index out of range");
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_sampler_scratch));
+    if (e != hipSuccess || !p) {
+      *why = std::string("hipGetSymbolAddress(sampler scratch): ") + hipGetErrorString(e);
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" int areal_sample_logprob_static(void* hip_stream, int32_t n, int32_t vocab, const float* logits,
+                                           const int32_t* seq_ids, const int32_t* positions, float temperature,
+                                           float top_p, uint64_t seed, const int32_t* forced,
+                                           int32_t* tokens_out, float* logp_behav, float* logp_full) {
+  if (n == 0) return AREAL_OK;
+  if (n < 0 || vocab <= 0 || !logits || !tokens_out || !logp_behav || (!forced && (!seq_ids || !positions))) {
+    areal::set_global_error("areal_sample_logprob_static: NULL argument, negative count or no vocabulary");
+    return AREAL_E_INVAL;
+  }
+  if (n > AREAL_SAMPLE_STATIC_MAX_ROWS || vocab > AREAL_SAMPLE_STATIC_MAX_VOCAB) {
+    areal::set_global_error("areal_sample_logprob_static: at most " +
+                            std::to_string(AREAL_SAMPLE_STATIC_MAX_ROWS) + " rows of at most " +
+                            std::to_string(AREAL_SAMPLE_STATIC_MAX_VOCAB) +
+                            " logits fit the static scratch buffer: split the batch, or use areal_sample_logprob");
+    return AREAL_E_NOMEM;
+  }
+  if (!(temperature > 0.f) || !(top_p > 0.f)) {
+    areal::set_global_error("areal_sample_logprob_static: temperature and top_p must be > 0");
+    return AREAL_E_INVAL;
+  }
+  std::string why;
+  void* scratch = static_scratch(&why);
+  if (!scratch) {
+    areal::set_global_error(why);
+    return AREAL_E_HIP;
+  }
+  const hipError_t e = areal::launch_sampler((hipStream_t)hip_stream, n, vocab, logits, seq_ids, positions,
+                                             1.0f / temperature, top_p, seed, forced, tokens_out, logp_behav,
+                                             logp_full, scratch);
+  if (e != hipSuccess) {
+    areal::set_global_error(std::string("areal_sample_logprob_static: ") + hipGetErrorString(e));
+    return e == hipErrorInvalidValue ? AREAL_E_INVAL : AREAL_E_HIP;
+  }
+  return AREAL_OK;
+}
