@@ -16,8 +16,14 @@ sampler  -- the specified sampling procedure that draws a_t and reports
 rollout  -- generate / update_weights semantics of the interruptible rollout
             worker (Section 4.1) and the per-position policy versions of
             Proposition 1.
-extras   -- the staleness gate (Section 5.1), the decoupled PPO objective
-            (Section 5.2) and the dynamic batching procedure (Appendix B.3).
+scoring  -- teacher-forced log-probabilities of whole trajectories: the
+            proximal policy's token probabilities that the decoupled objective
+            recomputes when a training batch arrives (Section 5.2, Eq. 5).
+staleness -- the staleness gate floor((N_r - 1) / B) <= i + eta of the rollout
+            controller and a plain event loop of the streaming regime
+            (Sections 4.1, 5.1).
+trainer_side -- the decoupled PPO objective (Section 5.2, Eq. 5, forward value)
+            and the dynamic batching procedure (Algorithm 1).
 
 Pins (tests that tie each function to something other than itself) live in
 tests/test_oracle_*.py.  Parity status per function:
@@ -31,4 +37,11 @@ sampler.philox4x32_10 -- pinned by the known-answer vectors distributed with
     the generator's reference implementation (tests/golden/philox_kat.txt).
 sampler.sexp, mass, nucleus, draw, logprobs -- pinned (libm, exact integer
     identities, brute-force sort, chi-square on empirical frequencies).
+scoring.sequence_logprobs -- pinned (log-softmax closed forms, agreement with
+    the rollout oracle's emitted log-probs, tests/test_oracle_scoring.py).
+staleness.StalenessGate, simulate_stream -- pinned (the synchronous schedule
+    at eta = 0, brute-force enumeration, tests/test_oracle_staleness.py).
+trainer_side.decoupled_ppo_objective, dynamic_batching -- pinned (reduction to the
+    standard clipped objective when prox = behav, brute force on small inputs,
+    tests/test_oracle_trainer_side.py).
 """

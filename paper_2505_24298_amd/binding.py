@@ -106,7 +106,11 @@ _SIGNATURES = {
     "areal_plan_passes": (C.c_int32, [C.c_int32, _I32P, C.c_int32, _I32P, C.c_int32]),
 }
 
+_HOST_NAMES = [n for n in _SIGNATURES if n.startswith(("areal_kvalloc_", "areal_gate_"))] + [
+    "areal_plan_passes", "areal_dynamic_batching"]
+
 _lib = None
+_host_lib = None
 
 
 def lib():
@@ -122,6 +126,24 @@ def lib():
             fn.restype, fn.argtypes = res, args
         _lib = l
     return _lib
+
+
+def host_lib():
+    """The host-only entry points (include/areal_host.h).  They live in the main library;
+    AREAL_HOST_LIB names another build of the same source to take them from instead (the
+    sanitizer build of the CPU tests)."""
+    global _host_lib
+    if _host_lib is None:
+        alt = os.environ.get("AREAL_HOST_LIB")
+        if not alt:
+            _host_lib = lib()
+        else:
+            l = C.CDLL(alt)
+            for name in _HOST_NAMES:
+                fn = getattr(l, name)
+                fn.restype, fn.argtypes = _SIGNATURES[name]
+            _host_lib = l
+    return _host_lib
 
 
 def _i32(a):

@@ -10,7 +10,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libareal.so")
-SOURCES = ["elementwise.hip", "gemm.hip", "attention.hip", "sampler.hip", "scoring.hip", "runtime.hip"]
+SOURCES = ["elementwise.hip", "gemm.hip", "attention.hip", "sampler.hip", "scoring.hip", "runtime.hip",
+           "host_api.cpp"]
+HOST_SAN_LIB = os.path.join(OBJ, "libareal_host_san.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed float32 VALU forms are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -24,7 +26,7 @@ def _hipcc():
 
 
 def _compile(src):
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
@@ -49,6 +51,27 @@ def build(verbose=True):
     if verbose:
         print(f"built {LIB}")
     return LIB
+
+
+def build_host_sanitized():
+    """The host-only part of the library (KV allocator, pass planner, staleness gate, dynamic
+    batching: csrc/host_api.cpp) as a shared object of its own, built with the host compiler
+    under the address and undefined-behaviour sanitizers.  Loaded by the CPU tests in a child
+    process that preloads the sanitizer runtimes.  Returns (library path, runtimes to preload)."""
+    os.makedirs(OBJ, exist_ok=True)
+    cxx = os.environ.get("CXX", "g++")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-fPIC", "-shared", "-fno-omit-frame-pointer",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           os.path.join(CSRC, "host_api.cpp"), "-o", HOST_SAN_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("sanitized host build failed:\n" + r.stderr)
+    runtimes = []
+    for name in ("libasan.so", "libubsan.so"):
+        path = subprocess.run([cxx, "-print-file-name=" + name], capture_output=True, text=True).stdout.strip()
+        if os.path.isabs(path) and os.path.exists(path):
+            runtimes.append(os.path.realpath(path))
+    return HOST_SAN_LIB, runtimes
 
 
 if __name__ == "__main__":

@@ -173,11 +173,15 @@ def test_bench_launch_configuration_sampled_sequences():
 
 
 # Rounding noise of the half-precision operands enters at every layer and adds in
-# quadrature through the depth, and it scales with the size of the logits: measured
-# at the 7B dimensions 1.1e-2 after 4 layers and 3.0e-2 after 28 (ratio = sqrt(7)),
-# with logits of standard deviation 1.2 against 0.78 at the 1.5B shape.  The stated
-# tolerances (2e-2 / 1e-2) are those of the 1.5B target shape; for the 7B shape at
-# full depth the bounds below are twice those: 3.3 % of a logit's standard deviation.
+# quadrature through the depth, and it scales with the size of the logits (standard
+# deviation 1.2 at hidden 3584 against 0.78 at the 1.5B shape).  The floor is pinned on the
+# CPU: tests/test_rounding_floor.py runs the oracle's layers at the 7B dimensions and all
+# 28 layers with nothing but the half-precision storage points rounded and measures logits
+# errors of rms 4.1e-3 and maximum 2.2e-2 (over 524,288 logits): the operand format alone
+# exceeds the 2e-2 stated for the 1.5B target shape, whatever the kernels do.  The GPU path
+# measures 2.95e-2 / 1.7e-2 here; the bounds below are twice the stated ones (3.3 % of a
+# logit's standard deviation).  At 4 layers of the same dimensions (test above) and at the
+# 1.5B shape (floor: rms 1.4e-3, maximum 6.5e-3) the stated bounds hold and are asserted.
 LOGIT_TOL_7B = 4e-2
 LOGP_TOL_7B = 2e-2
 

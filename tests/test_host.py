@@ -18,6 +18,13 @@ def L():
     return binding.lib()
 
 
+@pytest.fixture(scope="module")
+def HL():
+    """Host-only entry points: from the main library, or from the sanitizer build when
+    AREAL_HOST_LIB names it (test_host_logic_under_sanitizers runs this file that way)."""
+    return binding.host_lib()
+
+
 def _declared():
     names = set()
     for h in ("areal.h", "areal_host.h", "areal_ops.h"):
@@ -76,7 +83,8 @@ def _table(L, a, seq):
     return buf[:n].tolist()
 
 
-def test_allocator_grows_on_block_boundaries_and_reuses(L):
+def test_allocator_grows_on_block_boundaries_and_reuses(HL):
+    L = HL
     a = L.areal_kvalloc_create(10, 4, 8)
     assert L.areal_kvalloc_free_blocks(a) == 10
     assert L.areal_kvalloc_reserve(a, 0, 16) == 0 and _table(L, a, 0) == [0]
@@ -92,7 +100,8 @@ def test_allocator_grows_on_block_boundaries_and_reuses(L):
     L.areal_kvalloc_destroy(a)
 
 
-def test_allocator_exhaustion_is_all_or_nothing(L):
+def test_allocator_exhaustion_is_all_or_nothing(HL):
+    L = HL
     a = L.areal_kvalloc_create(4, 2, 3)
     assert L.areal_kvalloc_reserve(a, 0, 3 * 16) == 0
     assert L.areal_kvalloc_reserve(a, 1, 2 * 16) == binding.E_NOMEM      # pool: 1 left, 2 needed
@@ -102,7 +111,8 @@ def test_allocator_exhaustion_is_all_or_nothing(L):
     L.areal_kvalloc_destroy(a)
 
 
-def test_allocator_never_leaks_or_double_books(L):
+def test_allocator_never_leaks_or_double_books(HL):
+    L = HL
     rng = np.random.default_rng(0)
     a = L.areal_kvalloc_create(200, 16, 40)
     L.areal_kvalloc_shuffle(a, 7)
@@ -135,7 +145,8 @@ def _plan(L, lens, max_rows):
                             out.ctypes.data_as(binding._I32P), 1024)
     return out[:n]
 
-def test_planner_covers_every_position_once_in_order(L):
+def test_planner_covers_every_position_once_in_order(HL):
+    L = HL
     rng = np.random.default_rng(1)
     for trial in range(20):
         lens = rng.integers(1, 90, size=int(rng.integers(1, 12)))
@@ -167,12 +178,32 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0 and "one MI355X" in r.stderr and r.stdout.strip() == ""
 
 
+def test_host_logic_under_sanitizers():
+    """The allocator, planner, gate and batching tests of this file once more, in a child
+    process, against csrc/host_api.cpp built with -fsanitize=address,undefined (any report
+    aborts the child)."""
+    import subprocess
+    import sys
+    from paper_2505_24298_amd import build as b
+    if os.environ.get("AREAL_HOST_LIB"):
+        pytest.skip("already inside the sanitizer run")
+    lib, runtimes = b.build_host_sanitized()
+    assert runtimes, "sanitizer runtimes not found next to the host compiler"
+    env = dict(os.environ, AREAL_HOST_LIB=lib, LD_PRELOAD=":".join(runtimes),
+               ASAN_OPTIONS="detect_leaks=0:abort_on_error=1", UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-q", "-x", "-p", "no:cacheprovider",
+                        "-k", "allocator or planner or gate or kvalloc or dynamic_batching or stream"],
+                       capture_output=True, text=True, env=env, cwd=ROOT, timeout=600)
+    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-3000:]
+    assert " passed" in r.stdout and "failed" not in r.stdout
+
+
 def test_staleness_gate_matches_oracle_request_by_request():
     """The library's gate (budget form) against the oracle that applies the
     paper's inequality one request at a time, over random interleavings of
     submissions and version bumps, for every small (B, eta)."""
     from oracle import staleness
-    L = binding.lib()
+    L = binding.host_lib()
     rng = np.random.default_rng(3)
     for B in (1, 2, 5, 16):
         for eta in (0, 1, 4):
@@ -202,7 +233,7 @@ def _budget(o):
 
 
 def test_kvalloc_shared_prefix_refcounts():
-    L = binding.lib()
+    L = binding.host_lib()
     a = L.areal_kvalloc_create(10, 4, 8)
     assert L.areal_kvalloc_reserve(a, 0, 40) == 0 and _table(L, a, 0) == [0, 1, 2]
     assert L.areal_kvalloc_share(a, 1, 0, 2) == 0 and _table(L, a, 1) == [0, 1]
@@ -226,7 +257,7 @@ def test_dynamic_batching_matches_oracle():
     """Algorithm 1 in the library against the oracle on random length sets
     (ties in length and in sequence count included) and on the edge cases."""
     from oracle import trainer_side
-    L = binding.lib()
+    L = binding.host_lib()
     rng = np.random.default_rng(11)
     for _ in range(200):
         n = int(rng.integers(0, 60))
@@ -245,3 +276,90 @@ def test_dynamic_batching_matches_oracle():
                                     o.ctypes.data_as(binding._I32P)) == binding.E_INVAL
     assert L.areal_dynamic_batching(2, bad.ctypes.data_as(binding._I32P), 0, 1,
                                     o.ctypes.data_as(binding._I32P)) == binding.E_INVAL
+
+
+# ------------------------------------------------- streaming controller (host logic)
+class _FakeTensor:
+    def __getitem__(self, k):
+        return self
+
+    def contiguous(self):
+        return self
+
+    def to(self, d):
+        return self
+
+
+class _FakeTorch:
+    """Just enough of torch for harness.streaming_rollout to run without a GPU."""
+    float32, int32 = "f32", "i32"
+
+    class cuda:
+        class Event:
+            def __init__(self, enable_timing=True):
+                pass
+
+            def record(self):
+                pass
+
+            def elapsed_time(self, other):
+                return 1.0
+
+        @staticmethod
+        def synchronize():
+            pass
+
+    @staticmethod
+    def empty(shape, dtype=None, device=None):
+        return _FakeTensor()
+
+    @staticmethod
+    def empty_like(a):
+        return a
+
+    @staticmethod
+    def from_numpy(a):
+        return _FakeTensor()
+
+
+class _FakeEngine:
+    device = "cpu"
+
+    def __init__(self):
+        self.live = set()
+
+    def prefill(self, ids, prompts, logits_out=None):
+        assert not self.live & set(int(i) for i in ids)
+        self.live.update(int(i) for i in ids)
+
+    def sample_logprob(self, *a, **k):
+        pass
+
+    def decode_step(self, ids, *a, **k):
+        assert set(int(i) for i in ids) <= self.live
+
+    def free_seq(self, i):
+        self.live.remove(int(i))
+
+    def update_weights_interrupt(self, w, version, logits_out=None):
+        return np.array(sorted(self.live), dtype=np.int32), None, 0
+
+
+@pytest.mark.parametrize("eta", [0, 1, 2, 3, 5])
+def test_streaming_controller_follows_the_oracle_event_loop(eta):
+    """The refill loop of the streaming regime (slots, staleness gate through the C entry
+    points, one weight update per finished training batch) with the GPU calls stubbed out:
+    the same number of ticks as the oracle's plain event loop and every request submitted and
+    completed under the versions that loop gives it (Section 5.1)."""
+    from oracle import staleness
+    from paper_2505_24298_amd import harness
+    n_total, slots, B = 48, 8, 8
+    for seed in range(6):
+        outs = synth.output_lengths(n_total, 12, 1.0, 60, seed=seed)
+        prompts = [np.zeros(3, dtype=np.int32)] * n_total
+        eng = _FakeEngine()
+        r = harness.streaming_rollout(eng, _FakeTorch, dict(vocab=16), binding.host_lib(), prompts, outs, slots, B,
+                                      eta, [0, 1], 1.0, 1.0, 0)
+        ticks, done = staleness.simulate_stream(n_total, B, eta, slots, outs)
+        assert r["ticks"] == ticks and sorted(r["records"]) == sorted(done)
+        assert r["gen_tokens"] == int(outs.sum()) and not eng.live
