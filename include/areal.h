@@ -285,6 +285,11 @@ int areal_kv_blocks(areal_ctx* ctx, int64_t* total_out, int64_t* free_out);
  * token history is `fill_token`.  No forward pass runs.  Lets a decode step be
  * timed at a chosen context depth without generating up to it. */
 int areal_adopt_seq(areal_ctx* ctx, int32_t seq_id, int32_t len, int32_t fill_token);
+/* The same with the first n_shared_blocks KV blocks held together with the live sequence
+ * src_id (as the samples of one prompt share the prompt's blocks after areal_prefill):
+ * n_shared_blocks must be below the block count of `len` and at most what src_id holds. */
+int areal_adopt_seq_shared(areal_ctx* ctx, int32_t seq_id, int32_t len, int32_t fill_token,
+                           int32_t src_id, int32_t n_shared_blocks);
 
 /* Measurement hook (Section 3.2 motivates the roofline: decoding is memory-IO
  * bound).  Between areal_profile_begin and areal_profile_end the library

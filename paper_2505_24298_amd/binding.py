@@ -87,6 +87,7 @@ _SIGNATURES = {
     "areal_get_versions": (C.c_int, [C.c_void_p, C.c_int32, _I64P]),
     "areal_kv_blocks": (C.c_int, [C.c_void_p, _I64P, _I64P]),
     "areal_adopt_seq": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
+    "areal_adopt_seq_shared": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "areal_profile_begin": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
     "areal_profile_end": (C.c_int, [C.c_void_p, _I64P, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     # include/areal_ops.h
@@ -348,8 +349,9 @@ class Areal:
     def free_seq(self, seq_id):
         self._check(self.L.areal_free_seq(self.ctx, int(seq_id)))
 
-    def adopt_seq(self, seq_id, length, fill_token=0):
-        self._check(self.L.areal_adopt_seq(self.ctx, int(seq_id), int(length), int(fill_token)))
+    def adopt_seq(self, seq_id, length, fill_token=0, src_id=-1, n_shared_blocks=0):
+        self._check(self.L.areal_adopt_seq_shared(self.ctx, int(seq_id), int(length), int(fill_token),
+                                                  int(src_id), int(n_shared_blocks)))
 
     def seq_len(self, seq_id):
         v = C.c_int32()

@@ -1008,15 +1008,31 @@ int areal_kv_blocks(areal_ctx* c, int64_t* total, int64_t* free_) {
 }
 
 int areal_adopt_seq(areal_ctx* c, int32_t id, int32_t len, int32_t fill_token) {
+  return areal_adopt_seq_shared(c, id, len, fill_token, -1, 0);
+}
+
+int areal_adopt_seq_shared(areal_ctx* c, int32_t id, int32_t len, int32_t fill_token, int32_t src_id,
+                           int32_t n_shared_blocks) {
   if (!c) return AREAL_E_INVAL;
   const areal_model_cfg& g = c->cfg;
   if (id < 0 || id >= g.max_seqs || c->seqs[id].live) return fail(c, AREAL_E_INVAL, "sequence id out of range or live");
   if (len < 1 || len > g.max_seq_len) return fail(c, AREAL_E_INVAL, "bad length");
   if (fill_token < 0 || fill_token >= g.vocab) return fail(c, AREAL_E_INVAL, "token id outside the vocabulary");
-  if (c->alloc->extra_needed(id, len) > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
   const uint64_t nb = c->alloc->blocks_for(len);
+  if (n_shared_blocks > 0) {
+    if (src_id < 0 || src_id >= g.max_seqs || src_id == id || !c->seqs[src_id].live ||
+        (uint64_t)n_shared_blocks >= nb || (size_t)n_shared_blocks > c->alloc->blocks(src_id).size())
+      return fail(c, AREAL_E_INVAL, "shared blocks: source not live, or more blocks than it holds or than fit below the last");
+    if ((int64_t)nb - n_shared_blocks > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
+  } else if (c->alloc->extra_needed(id, len) > c->alloc->n_free()) {
+    return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
+  }
   int rc = ring_begin(c, align_up(nb * 4, 64));
   if (rc) return rc;
+  if (n_shared_blocks > 0) {
+    c->alloc->share_prefix(id, src_id, n_shared_blocks);
+    c->seqs[src_id].n_shared = std::max(c->seqs[src_id].n_shared, n_shared_blocks);
+  }
   c->alloc->reserve(id, len);
   Staged t = ring_take(c, nb * 4);
   memcpy(t.host, c->alloc->blocks(id).data(), nb * 4);
@@ -1030,6 +1046,7 @@ int areal_adopt_seq(areal_ctx* c, int32_t id, int32_t len, int32_t fill_token) {
   s.live = true;
   s.len = len;
   s.kv_len = len;
+  s.n_shared = std::max(0, n_shared_blocks);
   s.pending_version = c->version;
   s.versions.assign(len, -1);
   return AREAL_OK;

@@ -1,16 +1,25 @@
 #!/usr/bin/env python3
 """Single-kernel microbenchmarks on the MI355X (tuning and profiling aids).
 
-  python3 paper_2505_24298_amd/microbench.py attn-decode
+  python3 paper_2505_24298_amd/microbench.py attn-decode [shared]
       decode steps at the context mixes the qwen2-1.5b-rollout workload has after
       500 / 1500 / 3000 / 5000 / 7000 generated tokens (sequences adopted at those
       lengths, K/V pool filled with N(0,1)); reports the decode-attention launch
-      time and bandwidth (HIP events inside the library) and the step time.
+      time and bandwidth (HIP events inside the library) and the step time.  With
+      `shared` the samples of a prompt hold the prompt's KV blocks together, as after
+      areal_prefill of the workload (16 samples per prompt), and the line also gives
+      the distinct context tokens per launch.
+  python3 paper_2505_24298_amd/microbench.py gemm-chosen [M,M,...] [shape,...]
+      the projection GEMMs at the library's own tile choice only (a short run for
+      rocprofv3 --pmc: bytes fetched against weight bytes, matrix-core busy cycles).
   python3 paper_2505_24298_amd/microbench.py gemm [M,M,...] [shape,...]
       every tile configuration x K split of the projection GEMM at the decoder's
       shapes (qkv, o, gateup, down, lmhead of the 1.5B shape; qkv7 ... lmhead7 of the 7B shape);
       weights rotate over
       > 1 GB so they come from HBM.
+  python3 paper_2505_24298_amd/microbench.py copy
+      four plain 1 GiB device-to-device copies: the calibration of the FETCH_SIZE /
+      WRITE_SIZE counters (known bytes per dispatch).
   python3 paper_2505_24298_amd/microbench.py prefill [qwen2-1.5b|qwen2-7b]
       prefill of 32x256, 8x2048, 4x8000 tokens: per-kernel time of one layer.
   python3 paper_2505_24298_amd/microbench.py score
@@ -35,21 +44,32 @@ def _weights(torch, cfg):
     return device_weights(torch, cfg, 0, "cuda:0")
 
 
-def attn_decode():
+def attn_decode(shared=False):
     import torch
     from paper_2505_24298_amd import binding, synth
-    cfg, _, prompts, outs = synth.make_workload("qwen2-1.5b-rollout")
+    cfg, wl, prompts, outs = synth.make_workload("qwen2-1.5b-rollout")
     w = _weights(torch, cfg)
     kvb = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * 2
+    group = wl["samples"]
     for step in (500, 1500, 3000, 5000, 7000):
-        lens = [len(p) + step for p, o in zip(prompts, outs) if o > step]
+        live = [i for i, o in enumerate(outs) if o > step]
+        lens = [len(prompts[i]) + step for i in live]
         B = len(lens)
         eng = binding.Areal(cfg, max_seqs=B, max_seq_len=max(lens) + 64, max_batch_tokens=max(B, 256),
                             kv_blocks=sum(l // 16 + 6 for l in lens))
         eng.load_weights(w, 0)
         eng.kv_arena.view(torch.float16).normal_()
-        for s, l in enumerate(lens):
-            eng.adopt_seq(s, l, 1)
+        leader, distinct = {}, 0
+        for s, (i, l) in enumerate(zip(live, lens)):
+            g = i // group
+            n_sh = (len(prompts[i]) - 1) // 16
+            if shared and g in leader and n_sh > 0:
+                eng.adopt_seq(s, l, 1, src_id=leader[g], n_shared_blocks=n_sh)
+                distinct += l - 16 * n_sh
+            else:
+                eng.adopt_seq(s, l, 1)
+                leader.setdefault(g, s)
+                distinct += l
         ids = np.arange(B, dtype=np.int32)
         toks = torch.ones(B, dtype=torch.int32, device="cuda")
         for _ in range(3):
@@ -64,6 +84,7 @@ def attn_decode():
         cnt, ms, units = eng.profile_end()
         print(json.dumps(dict(after_tokens=step, sequences=B, mean_context=int(np.mean(lens)),
                               context_tokens_per_launch=int(units / cnt),
+                              distinct_context_tokens_per_launch=int(distinct + 3 * B + (n + 1) * B / 2),
                               attn_launch_us=round(ms / cnt * 1e3, 2),
                               attn_GBps=round(units * kvb / (ms * 1e-3) / 1e9, 1),
                               step_ms=round(e0.elapsed_time(e1) / n, 3))), flush=True)
@@ -71,16 +92,65 @@ def attn_decode():
         del eng
 
 
+def copy_calibration():
+    import torch
+    a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+    b = torch.empty_like(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    b.copy_(a)
+    e0.record()
+    for _ in range(3):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    print(json.dumps(dict(copies=4, bytes_each=1 << 30, GBps_read_plus_write=round(3 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1))))
+
+
+def gemm_chosen(ms_arg, shapes_arg, iters=20):
+    import torch
+    from paper_2505_24298_amd import binding
+    g = torch.Generator(device="cuda").manual_seed(0)
+    for name in shapes_arg.split(","):
+        N, K, mode = GEMM_SHAPES[name]
+        wbytes = N * K * 2 * (2 if mode == 2 else 1)
+        ncopy = max(2, min(64, int(1.2e9 // wbytes)))
+        mk = lambda: (torch.randn((N, K), generator=g, device="cuda") * 0.02).to(torch.float16)
+        Ws = [mk() for _ in range(ncopy)]
+        W1s = [mk() for _ in range(ncopy)] if mode == 2 else None
+        for M in [int(x) for x in ms_arg.split(",")]:
+            As = [torch.randn((M, K), generator=g, device="cuda").to(torch.float16) for _ in range(ncopy)]
+            Cs = [torch.zeros((M, N), device="cuda", dtype=torch.float16 if mode == 2 else torch.float32)
+                  for _ in range(ncopy)]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for it in range(2 * iters):
+                if it == iters:
+                    e0.record()
+                i = it % ncopy
+                binding.op_gemm(As[i], Ws[i], None if W1s is None else W1s[i], Cs[i], mode, -1,
+                                1 if name.startswith("lmhead") else -1)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / iters
+            print(json.dumps(dict(shape=name, M=M, launches=2 * iters, us=round(us, 2), weight_bytes=wbytes,
+                                  a_bytes=M * K * 2, weight_GBps=round(wbytes / us / 1e3, 1),
+                                  TFLOPs=round(2.0 * M * N * K * (2 if mode == 2 else 1) / us / 1e6, 1))), flush=True)
+            del As, Cs
+        del Ws, W1s
+
+
+GEMM_SHAPES = {"qkv": (2048, 1536, 0), "o": (1536, 1536, 1), "gateup": (8960, 1536, 2),
+               "down": (1536, 8960, 1), "lmhead": (151936, 1536, 0),
+               # the 7B shape
+               "qkv7": (4608, 3584, 0), "o7": (3584, 3584, 1), "gateup7": (18944, 3584, 2),
+               "down7": (3584, 18944, 1), "lmhead7": (152064, 3584, 0)}
+
+
 def gemm(ms_arg, shapes_arg):
     import torch
     from paper_2505_24298_amd import binding
     L = binding.lib()
     ncfg = L.areal_op_gemm_num_configs()
-    shapes = {"qkv": (2048, 1536, 0), "o": (1536, 1536, 1), "gateup": (8960, 1536, 2),
-              "down": (1536, 8960, 1), "lmhead": (151936, 1536, 0),
-              # the 7B shape
-              "qkv7": (4608, 3584, 0), "o7": (3584, 3584, 1), "gateup7": (18944, 3584, 2),
-              "down7": (3584, 18944, 1), "lmhead7": (152064, 3584, 0)}
+    shapes = GEMM_SHAPES
     Ms = [int(x) for x in ms_arg.split(",")]
     g = torch.Generator(device="cuda").manual_seed(0)
     for name in shapes_arg.split(","):
@@ -193,7 +263,12 @@ def score():
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else ""
     if what == "attn-decode":
-        attn_decode()
+        attn_decode(shared=len(sys.argv) > 2 and sys.argv[2] == "shared")
+    elif what == "copy":
+        copy_calibration()
+    elif what == "gemm-chosen":
+        gemm_chosen(sys.argv[2] if len(sys.argv) > 2 else "24,100,256",
+                    sys.argv[3] if len(sys.argv) > 3 else "qkv,o,gateup,down,lmhead")
     elif what == "gemm":
         gemm(sys.argv[2] if len(sys.argv) > 2 else "32,64,128,256",
              sys.argv[3] if len(sys.argv) > 3 else "qkv,o,gateup,down,lmhead")
