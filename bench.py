@@ -42,9 +42,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 / bf16
 SHAPE_LABEL = {"qwen2-1.5b": "Qwen2-1.5B", "qwen2-7b": "Qwen2-7B", "tiny": "tiny"}
-# HBM bytes the decode attention kernel moves per algorithmic K/V byte, from rocprofv3
-# FETCH_SIZE / WRITE_SIZE runs calibrated with a plain copy (profiles/attn_decode_kernel_hbm_traffic.md)
-ATTN_DECODE_FETCH_OVER_ALGORITHMIC = 1.024
+# HBM bytes the decode attention kernel moves, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# calibrated with a plain copy (profiles/attn_decode_kernel_hbm_traffic.md): bytes fetched per
+# byte of K/V that exists once in HBM (the samples of a prompt read the same prompt blocks; a
+# block is fetched about once per launch), and bytes written per per-sequence K/V byte read
+ATTN_DECODE_FETCH_OVER_DISTINCT = 1.033
 ATTN_DECODE_WRITE_OVER_ALGORITHMIC = 0.028
 
 
@@ -220,14 +222,21 @@ def summarise(args, cfg, wl, n, runs, warmups_done, copy_gbs, cpu_baseline, bind
     if args.profile_class == binding.K_ATTN_DECODE and pn:
         achieved = punits * kv_layer_bytes / (pms * 1e-3) / 1e9
         alg_per_launch = punits * kv_layer_bytes / pn
+        # every launch of a step reads the same contexts: whole-run averages per launch
+        ctx_all = sum(r["ctx_tokens"] for r in runs)
+        distinct_per_launch = alg_per_launch * sum(r["ctx_tokens_distinct"] for r in runs) / max(ctx_all, 1)
         roofline = dict(bound="hbm", kernel="attn_decode_kernel", achieved=round(achieved, 1),
                         peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
-                        traffic=int(alg_per_launch * (ATTN_DECODE_FETCH_OVER_ALGORITHMIC
-                                                      + ATTN_DECODE_WRITE_OVER_ALGORITHMIC)),
-                        traffic_unit="bytes per launch (counter ratios of profiles/attn_decode_kernel_hbm_traffic.md"
-                                     " x this run's algorithmic bytes per launch)",
+                        traffic=int(distinct_per_launch * ATTN_DECODE_FETCH_OVER_DISTINCT
+                                    + alg_per_launch * ATTN_DECODE_WRITE_OVER_ALGORITHMIC),
+                        traffic_unit="bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE of this kernel at this "
+                                     "workload's context mixes and block sharing, taken on microbench.py (the counter "
+                                     "profiler does not survive bench.py) as ratios to the K/V bytes that exist once "
+                                     "in HBM (fetch) and to the algorithmic bytes (write), applied to this run's bytes "
+                                     "per launch (profiles/attn_decode_kernel_hbm_traffic.md)",
                         frac_of_measured_copy=None if not copy_gbs else round(achieved / copy_gbs, 4),
                         algorithmic_bytes_per_launch=int(alg_per_launch),
+                        distinct_kv_bytes_per_launch=int(distinct_per_launch),
                         launches_timed=int(pn), avg_launch_us=round(pms / pn * 1e3, 2),
                         avg_context_tokens_per_launch=round(punits / pn, 1))
     else:
@@ -284,7 +293,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--budget-s", type=float, default=400.0,
+    ap.add_argument("--budget-s", type=float, default=360.0,
                     help="all-in wall-clock budget from process start; the timed rollouts stop when the next "
                          "one would not fit (at least one runs)")
     ap.add_argument("--warmup-scale", type=float, default=0.05,

@@ -7,7 +7,7 @@
 // in LDS, so the result does not depend on how the row was split.
 //
 // With few rows (fewer than half the compute units) and the whole vocabulary
-// kept (top-p = 1) a row is spread over several work-groups instead: partial
+// kept (top-p = 1) a row is spread over up to 64 work-groups instead: partial
 // maxima, then per-segment masses, go through a scratch buffer in device
 // memory, and a third launch scans the masses and picks the token.  The masses
 // are integers and the maximum is exact, so the token is the same either way.
@@ -28,7 +28,7 @@
 namespace areal {
 
 constexpr int SEG = 256, MAX_SEG = 1024;       // ids per segment, segments per row at most
-constexpr int SAMPLER_MAX_PARTS = 16;          // work-groups one row can be spread over
+constexpr int SAMPLER_MAX_PARTS = 64;          // work-groups one row can be spread over
 constexpr int SAMPLER_SPLIT_MAX_ROWS = AREAL_SAMPLE_STATIC_MAX_ROWS;   // rows the scratch buffer holds
 static_assert(AREAL_SAMPLE_STATIC_MAX_VOCAB == SEG * MAX_SEG, "header limit = segments x ids per segment");
 
@@ -525,9 +525,10 @@ hipError_t launch_sampler(hipStream_t s, int n, int vocab, const float* logits, 
       !logp_behav || !(inv_temperature > 0.f) || !(top_p > 0.f))
     return hipErrorInvalidValue;
   if (!forced && (!seq_ids || !positions)) return hipErrorInvalidValue;
-  // few rows, whole vocabulary kept: 2 .. 16 work-groups per row, about one per compute unit
+  // few rows, whole vocabulary kept: 2 .. 64 work-groups of four waves per row, about four per
+  // compute unit (the specified exponential is arithmetic-bound: it wants every SIMD's wave slots)
   const int nseg = (vocab + SEG - 1) / SEG;
-  int parts = std::min(SAMPLER_MAX_PARTS, 256 / n);
+  int parts = std::min(SAMPLER_MAX_PARTS, 1024 / n);
   parts = std::min(parts, (nseg + SPLIT_WAVES - 1) / SPLIT_WAVES);
   if (scratch && top_p >= 1.0f && n <= SAMPLER_SPLIT_MAX_ROWS && parts >= 2) {
     if ((uintptr_t)scratch & 15) return hipErrorInvalidValue;

@@ -111,7 +111,20 @@ def rollout(eng, torch, cfg, prompts, out_lens, temperature, top_p, seed, interr
     ev = lambda: torch.cuda.Event(enable_timing=True)
     e_start, e_prefill, e_end = ev(), ev(), ev()
     res = dict(prefill_tokens=int(plen.sum()), gen_tokens=int(out_lens.sum()), decode_steps=0,
-               decode_bytes=0.0, ctx_tokens=0, reprefill_tokens=0, interrupts=0, reprefill_ms=0.0)
+               decode_bytes=0.0, ctx_tokens=0, ctx_tokens_distinct=0, reprefill_tokens=0, interrupts=0,
+               reprefill_ms=0.0)
+    # samples of one prompt hold the prompt's full KV blocks together (all but the block with the
+    # last prompt token): positions that exist once in HBM however many live samples read them
+    keys = {}
+    group = np.array([keys.setdefault(np.asarray(p, dtype=np.int32).tobytes(), len(keys)) for p in prompts])
+    shared_len = np.array([((len(p) - 1) // 16) * 16 for p in prompts])
+
+    def distinct_ctx(live_n, gen_n):
+        g = group[:live_n]
+        first = np.zeros(live_n, dtype=bool)
+        first[np.unique(g, return_index=True)[1]] = True
+        return int((plen[:live_n] + gen_n).sum() - shared_len[:live_n][~first].sum())
+
     re_events = []
 
     torch.cuda.synchronize()
@@ -158,6 +171,7 @@ def rollout(eng, torch, cfg, prompts, out_lens, temperature, top_p, seed, interr
         eng.decode_step(ids[:live], toks[:live], logits_out=logits[:live])
         res["decode_bytes"] += decode_step_bytes(cfg, int((plen[:live] + gen).sum()), live)
         res["ctx_tokens"] += int((plen[:live] + gen).sum())
+        res["ctx_tokens_distinct"] += distinct_ctx(live, gen)
         res["decode_steps"] += 1
     e_end.record()
     torch.cuda.synchronize()

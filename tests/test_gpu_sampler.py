@@ -70,10 +70,10 @@ def test_masses_far_below_the_maximum_are_zero():
 
 @pytest.mark.parametrize("V", [151936, 5000])
 def test_rows_spread_over_work_groups(V):
-    """With few rows and top-p = 1 a row is spread over 2 .. 16 work-groups (partial maxima and
+    """With few rows and top-p = 1 a row is spread over 2 .. 64 work-groups (partial maxima and
     segment masses through a scratch buffer); 129 rows and more, and top-p < 1, keep one
-    work-group per row.  Token ids must not depend on the split: 1, 23 and 128 rows (16, 11
-    and 2 work-groups per row at the full vocabulary) against the oracle, and the same rows
+    work-group per row.  Token ids must not depend on the split: 1, 23 and 128 rows (64, 44
+    and 8 work-groups per row at the full vocabulary) against the oracle, and the same rows
     sampled as part of a batch of 129 (one work-group each) against the rows sampled alone."""
     import torch
     rng = np.random.default_rng(V)

@@ -27,9 +27,9 @@ def test_static_scratch_sampler_matches_the_context_entry_point():
     eng = binding.Areal(synth.shape("tiny", vocab=V), max_seqs=64, max_seq_len=32, max_batch_tokens=64,
                         kv_blocks=4)
     rng = np.random.default_rng(11)
-    first = (rng.standard_normal((100, V)) * 0.8).astype(np.float32)     # 2 work-groups per row
+    first = (rng.standard_normal((100, V)) * 0.8).astype(np.float32)     # 10 work-groups per row
     first[3] *= 8.0
-    second = (rng.standard_normal((9, V - 3000)) * 0.8).astype(np.float32)   # fewer rows, fewer segments, 16 per row
+    second = (rng.standard_normal((9, V - 3000)) * 0.8).astype(np.float32)   # fewer rows, fewer segments, 64 per row
     second = np.ascontiguousarray(np.pad(second, ((0, 0), (0, 3000)), constant_values=-30.0))
     for logits, seed in ((first, (7 << 32) | 5), (second, 123)):
         n = logits.shape[0]
