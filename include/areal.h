@@ -128,11 +128,12 @@ int areal_load_weights(areal_ctx* ctx, const areal_weights* w, uint64_t version)
  *   tokens     host [cu_seqlens[n_seqs]]  packed prompts, each length >= 1
  *   cu_seqlens host [n_seqs+1] prefix sums of the prompt lengths, [0] = 0
  *   logits_out device float32 [n_seqs, vocab]
- * Sequences of one call whose prompts are identical (the paper samples 16
- * answers per prompt, Table 3) share the KV blocks of the prompt: the first of
- * them computes the prompt, each of the others holds the same full blocks (all
- * but the block with the prompt's last token) and computes only the positions
- * after them.  Nothing else changes for the caller: every sequence has its own
+ * Sequences whose prompts are identical (the paper samples 16 answers per
+ * prompt, Table 3) share the KV blocks of the prompt, whether they arrive in
+ * one call or one by one while an earlier one is still live (the streaming
+ * regime of Section 4.1): the first of them computes the prompt, each of the
+ * others holds the same full blocks (all but the block with the prompt's last
+ * token) and computes only the positions after them.  Nothing else changes for the caller: every sequence has its own
  * id, logits row, history and later blocks, and a shared block returns to the
  * pool when its last holder terminates.  areal_update_weights_interrupt
  * recomputes a shared part once.

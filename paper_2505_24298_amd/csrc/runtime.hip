@@ -124,6 +124,11 @@ struct areal_ctx {
   int64_t n_blocks;
   KvAllocator* alloc = nullptr;
   std::vector<SeqInfo> seqs;
+  // prompts of the live sequences admitted by areal_prefill (host copies) and an index by
+  // prompt hash: a later call finds the live sequences that already hold a prompt's blocks
+  std::vector<std::vector<int32_t>> prompt_of;
+  std::vector<uint64_t> prompt_hash_of;
+  std::unordered_map<uint64_t, std::vector<int32_t>> prompt_index;
   WeightSet w;
   bool have_weights = false;
   int64_t version = 0;
@@ -573,6 +578,8 @@ int areal_create(const areal_model_cfg* cfg, areal_ctx** out) {
   c->geom.layer_stride = c->n_blocks * (int64_t)c->geom.block_stride;
   c->alloc = new KvAllocator(c->n_blocks, cfg->max_seqs, lay.max_blocks, AREAL_KV_BLOCK_TOKENS);
   c->seqs.resize(cfg->max_seqs);
+  c->prompt_of.resize(cfg->max_seqs);
+  c->prompt_hash_of.assign(cfg->max_seqs, 0);
   c->seg_bytes = lay.ring_bytes / kRingSegs;
   for (int i = 0; i < kRingSegs; ++i) { c->seg_done[i] = nullptr; c->seg_recorded[i] = false; }
   auto die = [&](hipError_t e, const char* what) {
@@ -649,10 +656,14 @@ int areal_prefill(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t
   if (cu[0] != 0) return fail(c, AREAL_E_INVAL, "cu_seqlens[0] must be 0");
   std::vector<char> seen(g.max_seqs, 0);
   // Prompt-prefix sharing (16 answers are sampled per prompt): a sequence whose prompt equals
-  // that of an earlier sequence of this call holds that sequence's full prompt blocks too and
-  // computes only what follows them.  One block fewer is shared when the prompt ends on a
-  // block boundary, so that every sequence has a last row of its own to produce logits from.
-  std::vector<int> leader(n, -1), n_sh(n, 0);
+  // that of an earlier sequence of this call, or of a sequence still live from an earlier call
+  // (the streaming regime admits the samples of a prompt one by one), holds that sequence's full
+  // prompt blocks too and computes only what follows them.  One block fewer is shared when
+  // the prompt ends on a block boundary, so that every sequence has a last row of its own to
+  // produce logits from.  Every live sequence's K/V was computed under the current parameters
+  // (a weight update recomputes all of them), so any live holder of the prompt will do.
+  std::vector<int> leader(n, -1), live_leader(n, -1), n_sh(n, 0);
+  std::vector<uint64_t> hashes(n, 0);
   {
     std::unordered_map<uint64_t, std::vector<int>> by_hash;
     for (int i = 0; i < n; ++i) {
@@ -660,14 +671,26 @@ int areal_prefill(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t
       if (len < 1) continue;                       // reported below
       uint64_t h = 1469598103934665603ull ^ (uint64_t)len;
       for (int64_t t = cu[i]; t < cu[i + 1]; ++t) h = (h ^ (uint32_t)tokens[t]) * 1099511628211ull;
+      hashes[i] = h;
       auto& bucket = by_hash[h];
       for (int j : bucket)
         if (cu[j + 1] - cu[j] == len && !memcmp(tokens + cu[j], tokens + cu[i], (size_t)len * 4)) {
           leader[i] = j;
-          n_sh[i] = (int)((len - 1) / AREAL_KV_BLOCK_TOKENS);
           break;
         }
-      if (leader[i] < 0) bucket.push_back(i);
+      if (leader[i] < 0) {
+        bucket.push_back(i);
+        auto it = c->prompt_index.find(h);
+        if (it != c->prompt_index.end())
+          for (int32_t id : it->second) {
+            const auto& p = c->prompt_of[id];
+            if ((int64_t)p.size() == len && !memcmp(p.data(), tokens + cu[i], (size_t)len * 4)) {
+              live_leader[i] = id;
+              break;
+            }
+          }
+      }
+      if (leader[i] >= 0 || live_leader[i] >= 0) n_sh[i] = (int)((len - 1) / AREAL_KV_BLOCK_TOKENS);
     }
   }
   int64_t need_blocks = 0;
@@ -691,9 +714,13 @@ int areal_prefill(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t
     const int id = seq_ids[i], len = cu[i + 1] - cu[i];
     const int shared_len = n_sh[i] * AREAL_KV_BLOCK_TOKENS;
     if (n_sh[i] > 0) {
-      const int lead_id = seq_ids[leader[i]];
+      // the holder the blocks and the history are taken from: a sequence live before this call
+      // where there is one (its history is already on the device; the first sample of this call
+      // with the same prompt takes its own shared part from there in the same launches)
+      const int lead_id = leader[i] < 0 ? live_leader[i]
+                          : (live_leader[leader[i]] >= 0 ? live_leader[leader[i]] : seq_ids[leader[i]]);
       c->alloc->share_prefix(id, lead_id, n_sh[i]);
-      c->seqs[lead_id].n_shared = n_sh[i];
+      c->seqs[lead_id].n_shared = std::max(c->seqs[lead_id].n_shared, n_sh[i]);
       const auto& lb = c->alloc->blocks(lead_id);
       for (int b = 0; b < n_sh[i]; ++b) { patches.push_back(id); patches.push_back(b); patches.push_back(lb[b]); }
       hist_jobs.push_back(id); hist_jobs.push_back(lead_id); hist_jobs.push_back(shared_len);
@@ -708,6 +735,9 @@ int areal_prefill(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int32_t
     s.versions.assign(len, -1);
     spans.push_back(Span{id, shared_len, len - shared_len, i});
     tok_off.push_back(cu[i] + shared_len);
+    c->prompt_of[id].assign(tokens + cu[i], tokens + cu[i + 1]);
+    c->prompt_hash_of[id] = hashes[i];
+    c->prompt_index[hashes[i]].push_back(id);
   }
   SeqState st = c->seq_state();
   if (!patches.empty()) {
@@ -974,6 +1004,15 @@ int areal_free_seq(areal_ctx* c, int32_t id) {
   if (id < 0 || id >= c->cfg.max_seqs || !c->seqs[id].live) return fail(c, AREAL_E_INVAL, "sequence not live");
   c->alloc->release(id);
   c->seqs[id] = SeqInfo();
+  if (!c->prompt_of[id].empty()) {
+    auto it = c->prompt_index.find(c->prompt_hash_of[id]);
+    if (it != c->prompt_index.end()) {
+      auto& v = it->second;
+      v.erase(std::remove(v.begin(), v.end(), id), v.end());
+      if (v.empty()) c->prompt_index.erase(it);
+    }
+    std::vector<int32_t>().swap(c->prompt_of[id]);
+  }
   return AREAL_OK;
 }
 

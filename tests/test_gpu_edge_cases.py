@@ -322,6 +322,74 @@ def test_shared_prompt_prefix_with_interrupt_and_early_termination(torch, bindin
     eng.close()
 
 
+def test_prompt_blocks_shared_across_prefill_calls(torch, binding):
+    """The streaming regime admits the samples of a prompt one by one: a sequence whose prompt
+    equals that of a sequence still live from an earlier call holds that sequence's prompt
+    blocks and computes only the rest.  The first holder then terminates (its blocks stay with
+    the others), a third sample arrives and shares with the second, a weight update recomputes
+    the shared part once, a sequence with a different prompt of the same length shares nothing.
+    Logits against the oracle throughout; block accounting at every step."""
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 33)
+    w2 = synth.perturb_weights(w, 1004, scale=5e-3, round_bf16=False)
+    rng = np.random.default_rng(14)
+    P = rng.integers(0, cfg["vocab"], size=53).astype(np.int32)           # 4 blocks, 3 shared
+    Q = P.copy()
+    Q[20] = (Q[20] + 1) % cfg["vocab"]                                    # same length, one token differs
+    eng = _engine(binding, cfg, w, kv_blocks=40)
+    wk = _oracle(cfg, w)
+    used = lambda: eng.kv_blocks()[0] - eng.kv_blocks()[1]
+    wk.add(0, P)
+    logits0 = eng.prefill([0], [P])
+    assert used() == 4
+    toks = _check_step(torch, eng, wk, [0], logits0)
+    logits0 = eng.decode_step([0], toks)
+    # second sample of P in a later call, together with a different prompt
+    wk.add(1, P)
+    wk.add(2, Q)
+    lg = eng.prefill([1, 2], [P, Q])
+    assert used() == 4 + 1 + 4                                            # 1: only its last block; 2: all four
+    assert eng.get_tokens(1).tolist() == P.tolist()
+    toks = _check_step(torch, eng, wk, [1, 2], lg)
+    lg12 = eng.decode_step([1, 2], toks)
+    toks = _check_step(torch, eng, wk, [0], logits0)
+    logits0 = eng.decode_step([0], toks)
+    # the first holder terminates: the shared blocks stay with sequence 1
+    eng.free_seq(0)
+    wk.finish(0)
+    assert used() == 3 + 1 + 4
+    wk.add(3, P)
+    wk.add(4, P)
+    lg3 = eng.prefill([3, 4], [P, P])                                     # two more samples in one call: both
+    assert used() == 3 + 1 + 4 + 1 + 1                                    # share with sequence 1
+    assert eng.get_tokens(3).tolist() == P.tolist() == eng.get_tokens(4).tolist()
+    toks3 = _check_step(torch, eng, wk, [3, 4], lg3)
+    toks = _check_step(torch, eng, wk, [1, 2], lg12)
+    eng.decode_step([1, 2], toks)
+    eng.decode_step([3, 4], toks3)
+    eng.free_seq(4)
+    wk.finish(4)
+    # weight update: the shared part is recomputed once (48 positions counted once)
+    wk.update_weights(_f16_weights(w2), 1)
+    live, logits, retok = eng.update_weights_interrupt(binding.weights_to_device(w2, bf16=False), 1)
+    assert live.tolist() == [1, 2, 3]
+    assert retok == sum(len(wk.tokens[s]) for s in (1, 2, 3)) - 48
+    for step in range(3):
+        toks = _check_step(torch, eng, wk, [1, 2, 3], logits.contiguous())
+        logits = eng.decode_step([1, 2, 3], toks)
+    for s in (1, 2, 3):
+        assert eng.get_tokens(s).tolist() == wk.tokens[s]
+        eng.free_seq(s)
+    assert used() == 0
+    # nothing stale in the index: the same prompt again computes everything
+    wk2 = _oracle(cfg, w2)
+    wk2.add(0, P)
+    lg = eng.prefill([0], [P])
+    assert used() == 4
+    _check_step(torch, eng, wk2, [0], lg)
+    eng.close()
+
+
 def test_half_precision_weights_in_place_and_tied_output_projection(torch, binding):
     """A context without the conversion workspace reads fp16 parameter sets where
     they are (also across a weight update); the output projection may be the

@@ -165,7 +165,7 @@ def test_errors_leave_state_unchanged(torch, binding):
     total, free = eng.kv_blocks()
     assert (total, free) == (3, 1)
     with pytest.raises(binding.ArealError) as e:
-        eng.prefill([1], p)                                      # needs 2 blocks, 1 free
+        eng.prefill([1], [p[0] + 1])                             # another prompt: needs 2 blocks, 1 free
     assert e.value.code == binding.E_NOMEM and eng.kv_blocks() == (3, 1) and eng.seq_len(1) == -1
     with pytest.raises(binding.ArealError) as e:
         eng.prefill([0], p)                                      # id already live
