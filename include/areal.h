@@ -90,7 +90,17 @@ typedef struct {
  * call that receives it (stream-ordered; bf16 values of magnitude >= 2^-14
  * convert exactly, smaller ones round to the nearest half subnormal, larger
  * than 65504 saturate) and is not read afterwards.
- * Per-layer arrays are host arrays of n_layers device pointers. */
+ * Per-layer arrays are host arrays of n_layers device pointers.
+ * Range: the values that become matrix-core operands or K/V-cache entries
+ * (normalised activations, q / k / v, attention output, SwiGLU output) are rounded
+ * to half precision too; magnitudes above 65,504 saturate to +-65,504 (no infinities
+ * are produced from finite values).  The residual stream, norm statistics,
+ * accumulators, softmax statistics and logits are float32.
+ * Reproducibility: projections whose K range is split over work-groups accumulate with
+ * float32 atomic adds in no fixed order, so logits can differ from run to run in the last
+ * bits (about 1e-7 relative); AREAL_GEMM_MAX_SPLITS=1 in the environment removes the splits,
+ * and with them the run-to-run differences, at a cost in decode speed.  The sampler is a
+ * pure function of the logits it is given. */
 typedef struct {
   int32_t dtype;                                    /* AREAL_DTYPE_F16, _BF16 or _F32        */
   const void *embed;                                /* [vocab, hidden]                       */

@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     const f16* __restrict__ bk, const f16* __restrict__ bv, const float* __restrict__ cos_tab,
     const float* __restrict__ sin_tab, f16* __restrict__ arena, KvGeom geom, int nq, int chunk,
     int n_splits, float scale_log2, float* __restrict__ part_o, float* __restrict__ part_ml,
-    f16* __restrict__ out) {
+    f16* __restrict__ out, const int32_t* __restrict__ step_table, int step_stride) {
   __shared__ float sm[4][16], sl[4][16];
   __shared__ float so[4][16][D];
   __shared__ float s_new[16], v_new[D];
@@ -227,8 +227,11 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   const int b0 = t0 / kBlockTokens;
   // the table entries of the whole split are requested at once with the row's position (entries
   // past the sequence's last block are stale but inside the table row, and never used)
-  const int32_t* table = st.table + (int64_t)rm.slot[i] * st.max_blocks;
-  const int b_cap = min(b0 + chunk / kBlockTokens, st.max_blocks);
+  // (with the per-step table, row i of which lists the blocks of this launch's row i, the
+  // address depends on the block index alone: one load fewer in front of the first tile)
+  const int32_t* table = step_table ? step_table + (int64_t)i * step_stride
+                                    : st.table + (int64_t)rm.slot[i] * st.max_blocks;
+  const int b_cap = min(b0 + chunk / kBlockTokens, step_table ? step_stride : st.max_blocks);
   BlockIds ids;
   ids.lo = b0 + lane < b_cap ? table[b0 + lane] : 0;
   ids.hi = b0 + 64 + lane < b_cap ? table[b0 + 64 + lane] : 0;
@@ -623,7 +626,9 @@ static bool geom_ok(const KvGeom& g, int nq) {
 hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
                               const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                               const float* sin_tab, f16* arena_layer, KvGeom geom, int n_q_heads,
-                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out) {
+                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out,
+                              const int32_t* step_table, int step_stride) {
+  if (step_table && step_stride <= 0) return hipErrorInvalidValue;
   if (M <= 0 || !geom_ok(geom, n_q_heads) || chunk <= 0 || chunk % (4 * NB * kBlockTokens) ||
       chunk > 128 * kBlockTokens || n_splits <= 0 || (n_splits > 1 && (!part_o || !part_ml)) ||
       !qkv || !cos_tab || !sin_tab || (bq && (!bk || !bv)) ||
@@ -634,7 +639,8 @@ hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm
 #define AREAL_DEC(DD)                                                                              \
   attn_decode_kernel<DD><<<grid, 256, 0, s>>>(qkv, rm, st, bq, bk, bv, cos_tab, sin_tab,           \
                                                arena_layer, geom, n_q_heads, chunk, n_splits,      \
-                                               scale_log2, part_o, part_ml, out);
+                                               scale_log2, part_o, part_ml, out, step_table,       \
+                                               step_stride);
   switch (geom.head_dim) {
     case 32: AREAL_DEC(32) break;
     case 64: AREAL_DEC(64) break;

@@ -57,13 +57,17 @@ __global__ __launch_bounds__(64) void rmsnorm_kernel(const float* __restrict__ x
   const int src = src_rows ? src_rows[row] : row;
   const float* xp = x + (int64_t)src * H;
   f32x4 v[NV];
+  f16x4 gn[NV];                       // the gains travel with the row: no second round trip after the sum
   float ss = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = (i * 64 + lane) * 4;
     v[i] = c < H ? *reinterpret_cast<const f32x4*>(xp + c) : f32x4{0.f, 0.f, 0.f, 0.f};
-    ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
+    gn[i] = c < H ? *reinterpret_cast<const f16x4*>(gain + c) : f16x4{0, 0, 0, 0};
   }
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+    ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
   if (zero_out) {
     float* zp = zero_out + (int64_t)row * zero_cols;
     const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
@@ -76,10 +80,9 @@ __global__ __launch_bounds__(64) void rmsnorm_kernel(const float* __restrict__ x
   for (int i = 0; i < NV; ++i) {
     const int c = (i * 64 + lane) * 4;
     if (c < H) {
-      const f16x4 g = *reinterpret_cast<const f16x4*>(gain + c);
       f16x4 o;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) o[k] = f2h_sat(v[i][k] * r * h2f(g[k]));
+      for (int k = 0; k < 4; ++k) o[k] = f2h_sat(v[i][k] * r * h2f(gn[i][k]));
       *reinterpret_cast<f16x4*>(yp + c) = o;
     }
   }

@@ -73,11 +73,14 @@ int attn_prefill_tile_rows(int n_q_heads, int n_kv_heads);   // 16 or 32
 // token's k happen inside, and the appended k, v are stored into the sequence's block
 // (table entry pos/16 must be installed).  Context = positions 0 .. pos.  `chunk` tokens per
 // split (multiple of 128, at most 2048); with n_splits > 1 the partials go to
-// `part_o` / `part_ml` and launch_attn_merge combines them into `out`.
+// `part_o` / `part_ml` and launch_attn_merge combines them into `out`.  `step_table`
+// (optional, device int32 [M, step_stride]): the block ids of row i's sequence, entries
+// 0 .. pos/16 at least, laid out by launch row; replaces the lookup through st.table.
 hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
                               const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                               const float* sin_tab, f16* arena_layer, KvGeom geom, int n_q_heads,
-                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out);
+                              int chunk, int n_splits, float* part_o, float* part_ml, f16* out,
+                              const int32_t* step_table = nullptr, int step_stride = 0);
 hipError_t launch_attn_merge(hipStream_t s, int M, RowMeta rm, int head_dim, int n_q_heads, int chunk,
                              int n_splits, const float* part_o, const float* part_ml, f16* out);
 hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work, int n_work,

@@ -84,7 +84,9 @@ Layout make_layout(const areal_model_cfg& c) {
   L.cos_t = take((uint64_t)c.max_seq_len * (d / 2) * 4);
   L.sin_t = take((uint64_t)c.max_seq_len * (d / 2) * 4);
   // per pass: slot, pos, token, new_block per row + work items + last rows
-  const uint64_t per_pass = M * 16 + (M / 16 + 2 * (uint64_t)c.max_seqs + 64) * 16 + (uint64_t)c.max_seqs * 16;
+  // (+ in a decode step the block ids of every row's sequence, laid out by row)
+  const uint64_t per_pass = M * 16 + (M / 16 + 2 * (uint64_t)c.max_seqs + 64) * 16 + (uint64_t)c.max_seqs * 16 +
+                            (uint64_t)c.max_seqs * (L.max_blocks + 4) * 4;
   L.ring_bytes = align_up(std::max<uint64_t>(per_pass * 2, 1u << 20), 4096) * kRingSegs;
   L.ring = take(L.ring_bytes);
   L.samp = take(sampler_scratch_bytes());
@@ -303,6 +305,8 @@ struct PassArgs {
   int n_out;                      // logits rows produced
   float* logits;                  // device [n_out, vocab]
   double attn_units;              // context tokens read (decode) / query-key pairs (prefill)
+  const int32_t* step_table = nullptr;   // decode: block ids by launch row (device), row stride below
+  int step_stride = 0;
   // scoring passes (teacher-forced log-probs of every row's next token)
   const int32_t* target = nullptr;   // device [M]: token each row predicts, -1 = none
   float inv_t = 1.f;
@@ -358,7 +362,7 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
         ProfScope ps(c, AREAL_K_ATTN_DECODE, l, sampled, a.attn_units);
         HIP_TRY(c, launch_attn_decode(s, qkv, a.M, a.rm, st, bq, bk, bv, cos_t, sin_t, arena_l, c->geom, nq,
                                       a.chunk, a.n_splits, c->wsp<float>(c->lay.part_o),
-                                      c->wsp<float>(c->lay.part_ml), attn));
+                                      c->wsp<float>(c->lay.part_ml), attn, a.step_table, a.step_stride));
       }
       if (a.n_splits > 1) {
         ProfScope ps(c, AREAL_K_ATTN_MERGE, l, sampled, rows);
@@ -773,12 +777,18 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
     need_blocks += c->alloc->extra_needed(id, c->seqs[id].len + 1);
   }
   if (need_blocks > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
-  int rc = ring_begin(c, align_up((uint64_t)n * 4, 64) * 3);
+  // per-step block table: row i lists the blocks of seq_ids[i] (the attention kernel then finds
+  // its block ids from the launch row alone, without going through the sequence's slot)
+  int longest = 0;
+  for (int i = 0; i < n; ++i) longest = std::max(longest, c->seqs[seq_ids[i]].len + 1);
+  const int tab_stride = (c->alloc->blocks_for(longest) + 3) / 4 * 4;
+  int rc = ring_begin(c, align_up((uint64_t)n * 4, 64) * 3 + align_up((uint64_t)n * tab_stride * 4, 64));
   if (rc) return rc;
   const uint64_t start = c->seg_used;
   Staged s_slot = ring_take(c, (uint64_t)n * 4), s_pos = ring_take(c, (uint64_t)n * 4),
-         s_nb = ring_take(c, (uint64_t)n * 4);
-  int32_t *hslot = (int32_t*)s_slot.host, *hpos = (int32_t*)s_pos.host, *hnb = (int32_t*)s_nb.host;
+         s_nb = ring_take(c, (uint64_t)n * 4), s_tab = ring_take(c, (uint64_t)n * tab_stride * 4);
+  int32_t *hslot = (int32_t*)s_slot.host, *hpos = (int32_t*)s_pos.host, *hnb = (int32_t*)s_nb.host,
+          *htab = (int32_t*)s_tab.host;
   int64_t sum_ctx = 0;
   int max_ctx = 0;
   for (int i = 0; i < n; ++i) {
@@ -787,9 +797,12 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
     const int pos = s.len;
     const size_t had = c->alloc->blocks(id).size();
     c->alloc->reserve(id, pos + 1);
+    const auto& blocks = c->alloc->blocks(id);
     hslot[i] = id;
     hpos[i] = pos;
-    hnb[i] = c->alloc->blocks(id).size() > had ? c->alloc->blocks(id).back() : -1;
+    hnb[i] = blocks.size() > had ? blocks.back() : -1;
+    memcpy(htab + (size_t)i * tab_stride, blocks.data(), blocks.size() * 4);
+    for (int b = (int)blocks.size(); b < tab_stride; ++b) htab[(size_t)i * tab_stride + b] = 0;
     s.versions.push_back(s.pending_version);
     s.len = pos + 1;
     s.kv_len = pos + 1;
@@ -822,6 +835,8 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
   a.n_out = n;
   a.logits = logits_out;
   a.attn_units = (double)sum_ctx;
+  a.step_table = (const int32_t*)s_tab.dev;
+  a.step_stride = tab_stride;
   return run_pass(c, a);
 }
 

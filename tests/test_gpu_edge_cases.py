@@ -390,6 +390,38 @@ def test_prompt_blocks_shared_across_prefill_calls(torch, binding):
     eng.close()
 
 
+def test_activations_beyond_the_half_range_saturate(torch, binding):
+    """Gate/up weights scaled so that the SwiGLU output exceeds 65,504, the largest half-
+    precision number: the values the kernels round to half on their way to the matrix cores
+    (normalised activations, q / k / v, attention output, SwiGLU output) saturate instead of
+    turning into infinities, so prefill and decode logits stay finite and the sampler still
+    returns tokens of the vocabulary.  (Without saturation the first such value makes the
+    residual row, and every logit after it, NaN.)"""
+    cfg = synth.shape("tiny")
+    w = synth.make_weights(cfg, 41)
+    for lw in w["layers"]:
+        lw["wgate"] = lw["wgate"] * np.float32(3000.0)
+        lw["wup"] = lw["wup"] * np.float32(3000.0)
+    # the products really leave the range: float64 SwiGLU of the first block's input
+    from oracle import decoder
+    x = decoder.rmsnorm(w["embed"][:64], w["layers"][0]["norm_ffn"], cfg["rms_eps"])
+    act = decoder.silu(x @ _f16(w["layers"][0]["wgate"]).T.astype(np.float64)) * (
+        x @ _f16(w["layers"][0]["wup"]).T.astype(np.float64))
+    assert np.abs(act).max() > 10 * 65504.0
+    eng = _engine(binding, cfg, w)
+    prompts = synth.make_prompts(cfg, 3, 1, 20, 40, seed=42)
+    ids = [0, 1, 2]
+    logits = eng.prefill(ids, prompts)
+    for step in range(4):
+        assert bool(torch.isfinite(logits).all())
+        toks, lb, lf = eng.sample_logprob(logits, ids, [len(p) + step for p in prompts], 1.0, 1.0, 3)
+        t = toks.cpu().numpy()
+        assert ((t >= 0) & (t < cfg["vocab"])).all() and bool(torch.isfinite(lb).all())
+        logits = eng.decode_step(ids, toks)
+    assert bool(torch.isfinite(logits).all())
+    eng.close()
+
+
 def test_half_precision_weights_in_place_and_tied_output_projection(torch, binding):
     """A context without the conversion workspace reads fp16 parameter sets where
     they are (also across a weight update); the output projection may be the
