@@ -290,6 +290,17 @@ int areal_get_tokens(areal_ctx* ctx, int32_t seq_id, int32_t* tokens_out /* host
  * produced the token (Proposition 1). */
 int areal_get_versions(areal_ctx* ctx, int32_t seq_id, int64_t* versions_out /* host [len] */);
 int areal_kv_blocks(areal_ctx* ctx, int64_t* total_out, int64_t* free_out);
+/* Decode attention can walk KV blocks that several rows of a step hold together (the samples
+ * of one prompt, Table 3: 16 answers per prompt) once per set of rows and not once per row.
+ * It does so in the steps where at least 70 % of the context tokens read are shared in this
+ * way; AREAL_DECODE_GROUPS=1 / 0 in the environment at areal_create makes it always / never.
+ * The result is the same up to float32 summation order.
+ * Sums over the decode steps since areal_create (any pointer may be NULL):
+ *   rows_out        rows that were part of a set,
+ *   row_tokens_out  context tokens of those rows that their set walked for them,
+ *   set_tokens_out  context tokens the sets walked (each set once). */
+int areal_decode_set_counters(areal_ctx* ctx, int64_t* rows_out, int64_t* row_tokens_out,
+                              int64_t* set_tokens_out);
 
 /* Benchmark helper: make `seq_id` a live sequence of `len` tokens whose K/V are
  * taken to be whatever the arena blocks assigned to it already hold and whose

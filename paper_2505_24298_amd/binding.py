@@ -86,6 +86,7 @@ _SIGNATURES = {
     "areal_get_tokens": (C.c_int, [C.c_void_p, C.c_int32, _I32P]),
     "areal_get_versions": (C.c_int, [C.c_void_p, C.c_int32, _I64P]),
     "areal_kv_blocks": (C.c_int, [C.c_void_p, _I64P, _I64P]),
+    "areal_decode_set_counters": (C.c_int, [C.c_void_p, _I64P, _I64P, _I64P]),
     "areal_adopt_seq": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
     "areal_adopt_seq_shared": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "areal_profile_begin": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
@@ -380,6 +381,11 @@ class Areal:
         t, f = C.c_int64(), C.c_int64()
         self._check(self.L.areal_kv_blocks(self.ctx, C.byref(t), C.byref(f)))
         return t.value, f.value
+
+    def decode_set_counters(self):
+        r, rt, st = C.c_int64(), C.c_int64(), C.c_int64()
+        self._check(self.L.areal_decode_set_counters(self.ctx, C.byref(r), C.byref(rt), C.byref(st)))
+        return r.value, rt.value, st.value
 
 
 def sample_logprob_static(logits, seq_ids, positions, temperature=1.0, top_p=1.0, seed=0, forced_tokens=None,

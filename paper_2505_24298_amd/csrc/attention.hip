@@ -201,6 +201,88 @@ __device__ __forceinline__ void rotate(RawHead<D>& r, const f16* __restrict__ bi
   }
 }
 
+// The leading KV blocks that a set of rows has in common (work-groups blockIdx.x >= n_splits of
+// the decode launch: x - n_splits = chunk of the shared part, y = kv head, z = set).  Wave w
+// owns tile w of the set: 16 MFMA rows = floor(16 / G) sequences x their G query heads, so
+// every lane has its own sequence, position and query head.  Each wave walks all blocks of the
+// chunk (the four waves read the same tiles: one fetch from L2 per work-group) and writes
+// its rows' partial (max, sum, accumulator) into slot n_splits + chunk of those rows; the
+// merge kernel folds them into the rows' own partials.  Every shared position precedes every
+// row's position, so nothing is masked but the tail of the last block pair.  Block ids: row
+// M + set of the per-step table.
+template <int D>
+__device__ __forceinline__ void decode_shared_set(
+    const float* __restrict__ qkv, const RowMeta& rm, const f16* __restrict__ bq,
+    const float* __restrict__ cos_tab, const float* __restrict__ sin_tab,
+    const f16* __restrict__ arena, const KvGeom& geom, int nq, int n_splits, int n_slots,
+    float scale_log2, float* __restrict__ part_o, float* __restrict__ part_ml,
+    const int32_t* __restrict__ step_table, int step_stride, const DecodeGroups& grp, int M) {
+  const int set = blockIdx.z, kvh = blockIdx.y, u = (int)blockIdx.x - n_splits;
+  if (set >= grp.n_sets) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane >> 4, j = lane & 15;
+  const int nkv = geom.n_kv_heads, G = nq / nkv, P = 16 / G;
+  const int chunk = grp.sh_chunk;
+  const int t0 = u * chunk, b0 = t0 / kBlockTokens;
+  const int32_t* table = step_table + (int64_t)(M + set) * step_stride;
+  const int b_cap = min(b0 + chunk / kBlockTokens, step_stride);
+  BlockIds ids;
+  ids.lo = b0 + lane < b_cap ? table[b0 + lane] : 0;
+  ids.hi = b0 + 64 + lane < b_cap ? table[b0 + 64 + lane] : 0;
+  const int sq = j / G;                                  // sequence of this lane's row inside the tile
+  const int r = sq < P ? grp.set_rows[((int64_t)set * kGroupTiles + wave) * 16 + sq] : -1;
+  const int ts = grp.set_start[set];
+  if (t0 >= ts) return;
+  if (__ballot(r >= 0) == 0) return;                     // no tile for this wave
+  const int t1 = min(ts, t0 + chunk);
+  const int b1 = (t1 + kBlockTokens - 1) / kBlockTokens;
+  const int rr = max(r, 0);                              // empty rows read row 0 and are zeroed below
+  const int pos = rm.pos[rr];
+  const int head = kvh * G + (j - sq * G);
+  RawHead<D> qraw;
+  load_raw<D>(qraw, qkv + ((int64_t)rr * (nq + 2 * nkv) + head) * D, g);
+  RopeAngles<D> ang;
+  load_angles<D>(ang, cos_tab + (int64_t)pos * (D / 2), sin_tab + (int64_t)pos * (D / 2), g);
+  int b = b0;
+  KvFrag<D> cur, nxt;
+  load_group_ids<D>(cur, arena, geom, ids, b0, b, b1, kvh, lane);
+  f16x8 qf[D / 32];
+  rotate<D>(qraw, bq ? bq + head * D : nullptr, ang, g, qf);
+  if (r < 0) {
+    const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c) qf[c] = zero8;
+  }
+  float m = -INFINITY, l = 0.f;
+  f32x4 o[D / 16];
+#pragma unroll
+  for (int n = 0; n < D / 16; ++n) o[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+  while (b < b1) {
+    const int bn = b + NB;
+    if (bn < b1) load_group_ids<D>(nxt, arena, geom, ids, b0, bn, b1, kvh, lane);
+    attend_group<D>(cur, qf, b, t1 - 1, scale_log2, m, l, o, lane);
+    cur = nxt;
+    b = bn;
+  }
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  const int slot = n_splits + u;
+  if (g == 0 && r >= 0) {
+    const int64_t pi = ((int64_t)r * nq + head) * n_slots + slot;
+    part_ml[pi * 2] = m;
+    part_ml[pi * 2 + 1] = l;
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {                          // accumulator row 4g+v belongs to lane 4g+v's row
+    const int r_v = __shfl(r, 4 * g + v), head_v = __shfl(head, 4 * g + v);
+    if (r_v >= 0) {
+      const int64_t pi = ((int64_t)r_v * nq + head_v) * n_slots + slot;
+#pragma unroll
+      for (int n = 0; n < D / 16; ++n) part_o[pi * D + 16 * n + j] = o[n][v];
+    }
+  }
+}
+
 // One work-group per (split, kv head, sequence); the partials of a sequence cut
 // into several splits are combined by attn_merge_kernel.  The row's query heads
 // are taken from the float32 QKV row (bias, RoPE, rounding done here).  The
@@ -215,14 +297,24 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
     const f16* __restrict__ bk, const f16* __restrict__ bv, const float* __restrict__ cos_tab,
     const float* __restrict__ sin_tab, f16* __restrict__ arena, KvGeom geom, int nq, int chunk,
     int n_splits, float scale_log2, float* __restrict__ part_o, float* __restrict__ part_ml,
-    f16* __restrict__ out, const int32_t* __restrict__ step_table, int step_stride) {
+    f16* __restrict__ out, const int32_t* __restrict__ step_table, int step_stride, DecodeGroups grp) {
   __shared__ float sm[4][16], sl[4][16];
   __shared__ float so[4][16][D];
   __shared__ float s_new[16], v_new[D];
+  const int n_slots = n_splits + grp.n_shared;           // partial slots per (row, head)
+  if ((int)blockIdx.x >= n_splits) {                     // the shared leading blocks of a set of rows
+    if ((int)blockIdx.x >= n_slots) return;             // padding column (the launch keeps gridDim.x odd)
+    decode_shared_set<D>(qkv, rm, bq, cos_tab, sin_tab, arena, geom, nq, n_splits, n_slots,
+                         scale_log2, part_o, part_ml, step_table, step_stride, grp, (int)gridDim.z);
+    return;
+  }
   const int i = blockIdx.z, kvh = blockIdx.y, split = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, j = lane & 15;
   const int nkv = geom.n_kv_heads, G = nq / nkv;
+  // Token and block indices below are relative to the first position this row's own
+  // work-groups cover (t_start, a multiple of the block size; the row of the per-step table
+  // starts at that block too), so that no address depends on t_start.
   const int t0 = split * chunk;
   const int b0 = t0 / kBlockTokens;
   // the table entries of the whole split are requested at once with the row's position (entries
@@ -235,7 +327,8 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   BlockIds ids;
   ids.lo = b0 + lane < b_cap ? table[b0 + lane] : 0;
   ids.hi = b0 + 64 + lane < b_cap ? table[b0 + 64 + lane] : 0;
-  const int pos = rm.pos[i];
+  const int pos_abs = rm.pos[i];
+  const int pos = pos_abs - (grp.t_start ? grp.t_start[i] : 0);
   if (t0 > pos) return;
   const bool owner = pos < t0 + chunk;                 // this split holds the appended position
   const int t1 = min(pos, t0 + chunk);                 // cached tokens [t0, t1)
@@ -248,7 +341,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
   RawHead<D> qraw;
   load_raw<D>(qraw, row + head * D, g);
   RopeAngles<D> ang;
-  load_angles<D>(ang, cos_tab + (int64_t)pos * (D / 2), sin_tab + (int64_t)pos * (D / 2), g);
+  load_angles<D>(ang, cos_tab + (int64_t)pos_abs * (D / 2), sin_tab + (int64_t)pos_abs * (D / 2), g);
 
   // wave w takes block groups w, w+4, ... of this split
   int b = b0 + wave * NB;
@@ -332,10 +425,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
       M = M2;
     }
     const int head = kvh * G + h;
-    if (n_splits == 1) {
+    if (n_slots == 1) {
       out[((int64_t)i * nq + head) * D + dd] = f2h_sat(O / L);
     } else {
-      const int64_t pi = ((int64_t)i * nq + head) * n_splits + split;
+      const int64_t pi = ((int64_t)i * nq + head) * n_slots + split;
       part_o[pi * D + dd] = O;
       if (dd == 0) { part_ml[pi * 2] = M; part_ml[pi * 2 + 1] = L; }
     }
@@ -345,42 +438,51 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(
 // Combine the split partials of one (row, head): out = sum_s O_s 2^(M_s-M) / sum_s L_s 2^(M_s-M).
 // Every load address depends only on the launch shape, so the row's position, the
 // statistics (lane s fetches (M_s, L_s)) and the first eight partial rows all go out
-// together; which splits really exist (ns) is applied afterwards by selection.  Slots of
-// splits beyond ns hold stale values of earlier launches: selected away, never multiplied.
+// together; which slots really exist for this row is applied afterwards by selection.  The
+// other slots hold stale values of earlier launches: selected away, never multiplied.
 template <int D>
 __global__ __launch_bounds__(D < 64 ? 64 : D) void attn_merge_kernel(const float* __restrict__ part_o,
                                                        const float* __restrict__ part_ml, RowMeta rm,
-                                                       int nq, int chunk, int n_splits,
+                                                       int nq, int chunk, int n_splits, int n_shared,
+                                                       int sh_chunk, const int32_t* __restrict__ t_start,
                                                        f16* __restrict__ out) {
   constexpr int BATCH = 8;
+  const int n_slots = n_splits + n_shared;                    // <= 32
   const int i = blockIdx.x / nq;
-  const int64_t base = (int64_t)blockIdx.x * n_splits;
+  const int64_t base = (int64_t)blockIdx.x * n_slots;
   const int lane = threadIdx.x & 63;
   const int dd = min((int)threadIdx.x, D - 1);
   const float* po = part_o + base * D + dd;
-  const int pos = rm.pos[i];
+  const int pos_abs = rm.pos[i];
+  const int ts = t_start ? t_start[i] : 0;
   float2 ml = {0.f, 0.f};
-  if (lane < n_splits) ml = *reinterpret_cast<const float2*>(part_ml + (base + lane) * 2);
+  if (lane < n_slots) ml = *reinterpret_cast<const float2*>(part_ml + (base + lane) * 2);
   float v[BATCH], vn[BATCH];
 #pragma unroll
-  for (int u = 0; u < BATCH; ++u) v[u] = u < n_splits ? po[(int64_t)u * D] : 0.f;
+  for (int u = 0; u < BATCH; ++u) v[u] = u < n_slots ? po[(int64_t)u * D] : 0.f;
 
-  const int ns = min(n_splits, (pos + chunk) / chunk);      // splits of this row: ceil((pos+1)/chunk) <= 32
-  const float ms = lane < ns ? ml.x : -INFINITY, ls = lane < ns ? ml.y : 0.f;
+  // slots of this row: its own splits 0 .. ceil((pos + 1 - ts) / chunk) - 1, then the chunks of
+  // the part it shares with its set (slot n_splits + u exists while u * chunk < ts)
+  const int ns = min(n_splits, (pos_abs - ts + chunk) / chunk);
+  const bool mine = lane < n_splits ? lane < ns : (lane < n_slots && (lane - n_splits) * sh_chunk < ts);
+  const uint64_t have = __ballot(mine);                       // slots live in lanes 0 .. 31
+  const float ms = mine ? ml.x : -INFINITY, ls = mine ? ml.y : 0.f;
   const float M = wave_max(ms);                               // whole waves only: blockDim >= 64
-  const float sc = __builtin_amdgcn_exp2f(ms - M);           // lanes >= ns: 2^-inf = 0
+  const float sc = __builtin_amdgcn_exp2f(ms - M);           // other lanes: 2^-inf = 0
   const float L = wave_sum(ls * sc);
   float O = 0.f;
-  for (int s0 = 0; s0 < ns; s0 += BATCH) {
-    if (s0 + BATCH < ns) {                                    // next batch in flight while this one is used
+  for (int s0 = 0; s0 < n_slots; s0 += BATCH) {
+    const bool more = (have >> (s0 + BATCH)) != 0 && s0 + BATCH < n_slots;
+    if (more) {                                               // next batch in flight while this one is used
 #pragma unroll
-      for (int u = 0; u < BATCH; ++u) vn[u] = s0 + BATCH + u < n_splits ? po[(int64_t)(s0 + BATCH + u) * D] : 0.f;
+      for (int u = 0; u < BATCH; ++u) vn[u] = s0 + BATCH + u < n_slots ? po[(int64_t)(s0 + BATCH + u) * D] : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) {
       const float w = __shfl(sc, (s0 + u) & 31);
-      O += s0 + u < ns ? v[u] * w : 0.f;
+      O += ((have >> (s0 + u)) & 1u) ? v[u] * w : 0.f;
     }
+    if (!more) break;
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) v[u] = vn[u];
   }
@@ -623,24 +725,35 @@ static bool geom_ok(const KvGeom& g, int nq) {
   return true;
 }
 
+static bool groups_ok(const DecodeGroups& grp, int M, int n_splits, const int32_t* step_table) {
+  if (grp.n_sets == 0 && grp.n_shared == 0 && !grp.t_start) return true;
+  return grp.n_sets > 0 && grp.n_sets <= M && grp.n_shared > 0 && n_splits + grp.n_shared <= 32 &&
+         grp.sh_chunk > 0 && grp.sh_chunk % (NB * kBlockTokens) == 0 && grp.sh_chunk <= 128 * kBlockTokens &&
+         grp.t_start && grp.set_rows && grp.set_start && step_table;
+}
+
 hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
                               const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                               const float* sin_tab, f16* arena_layer, KvGeom geom, int n_q_heads,
                               int chunk, int n_splits, float* part_o, float* part_ml, f16* out,
-                              const int32_t* step_table, int step_stride) {
+                              const int32_t* step_table, int step_stride, DecodeGroups grp) {
   if (step_table && step_stride <= 0) return hipErrorInvalidValue;
   if (M <= 0 || !geom_ok(geom, n_q_heads) || chunk <= 0 || chunk % (4 * NB * kBlockTokens) ||
-      chunk > 128 * kBlockTokens || n_splits <= 0 || (n_splits > 1 && (!part_o || !part_ml)) ||
+      chunk > 128 * kBlockTokens || n_splits <= 0 || !groups_ok(grp, M, n_splits, step_table) ||
+      (n_splits + grp.n_shared > 1 && (!part_o || !part_ml)) ||
       !qkv || !cos_tab || !sin_tab || (bq && (!bk || !bv)) ||
       (((uintptr_t)qkv | (uintptr_t)bq | (uintptr_t)bk | (uintptr_t)bv | (uintptr_t)arena_layer) & 15))
     return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)geom.head_dim);
-  dim3 grid(n_splits, geom.n_kv_heads, M);
+  // Work-groups go to the eight XCDs round-robin in launch order (x fastest).  With an even
+  // gridDim.x a split index would always land on the same few XCDs, and the low splits, which
+  // every row has, would crowd them; an odd gridDim.x rotates the assignment row by row.
+  dim3 grid((n_splits + grp.n_shared) | 1, geom.n_kv_heads, M);
 #define AREAL_DEC(DD)                                                                              \
   attn_decode_kernel<DD><<<grid, 256, 0, s>>>(qkv, rm, st, bq, bk, bv, cos_tab, sin_tab,           \
                                                arena_layer, geom, n_q_heads, chunk, n_splits,      \
                                                scale_log2, part_o, part_ml, out, step_table,       \
-                                               step_stride);
+                                               step_stride, grp);
   switch (geom.head_dim) {
     case 32: AREAL_DEC(32) break;
     case 64: AREAL_DEC(64) break;
@@ -651,13 +764,16 @@ hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm
 }
 
 hipError_t launch_attn_merge(hipStream_t s, int M, RowMeta rm, int head_dim, int n_q_heads, int chunk,
-                             int n_splits, const float* part_o, const float* part_ml, f16* out) {
-  if (M <= 0 || n_splits < 2 || n_splits > 32 || chunk <= 0 || !part_o || !part_ml || !out ||
-      (head_dim != 32 && head_dim != 64 && head_dim != 128))
+                             int n_splits, const float* part_o, const float* part_ml, f16* out,
+                             DecodeGroups grp) {
+  const int n_slots = n_splits + grp.n_shared;
+  if (M <= 0 || n_splits < 1 || n_slots < 2 || n_slots > 32 || chunk <= 0 || !part_o || !part_ml || !out ||
+      (grp.n_shared > 0 && (!grp.t_start || grp.sh_chunk <= 0)) || (head_dim != 32 && head_dim != 64 && head_dim != 128))
     return hipErrorInvalidValue;
 #define AREAL_MRG(DD)                                                                              \
   attn_merge_kernel<DD><<<M * n_q_heads, DD < 64 ? 64 : DD, 0, s>>>(part_o, part_ml, rm, n_q_heads, \
-                                                                    chunk, n_splits, out);
+                                                                    chunk, n_splits, grp.n_shared,  \
+                                                                    grp.sh_chunk, grp.t_start, out);
   switch (head_dim) {
     case 32: AREAL_MRG(32) break;
     case 64: AREAL_MRG(64) break;

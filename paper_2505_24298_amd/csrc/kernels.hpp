@@ -68,21 +68,40 @@ struct AttnWork {              // prefill work item: a tile of consecutive query
   int32_t slot, row0, pos0, n_rows;   // n_rows <= attn_prefill_tile_rows()
 };
 int attn_prefill_tile_rows(int n_q_heads, int n_kv_heads);   // 16 or 32
+// Rows of a decode launch whose sequences hold the same leading KV blocks (the samples of one
+// prompt): those blocks are walked once per set of rows instead of once per row.  A set is up
+// to kGroupTiles MFMA tiles of 16 rows = floor(16 / G) sequences x G query heads each; the
+// work-groups of the sets are part of the same launch.  All arrays are device memory.
+constexpr int kGroupTiles = 4;
+struct DecodeGroups {
+  const int32_t* t_start = nullptr;   // [M] leading tokens of row i that its set covers (multiple of 16; 0: none)
+  const int32_t* set_rows = nullptr;  // [n_sets][kGroupTiles][16] launch rows of tile t (first floor(16/G) entries
+                                      // used, -1 = empty; entry 0 of tile 0 is valid: its blocks are the ones walked)
+  const int32_t* set_start = nullptr; // [n_sets] the t_start of the set's rows
+  int n_sets = 0;                     // <= M
+  int sh_chunk = 0;                   // tokens of the shared part per work-group (multiple of 32, at most 2048)
+  int n_shared = 0;                   // partial slots per row for the shared part: ceil(max t_start / sh_chunk)
+};
 // decode: one query row per sequence (row i <-> rm.slot[i], rm.pos[i]), taken from the float32
 // QKV rows [M, (nq + 2 nkv) d] of the pass: bias, RoPE and rounding of q and of the appended
 // token's k happen inside, and the appended k, v are stored into the sequence's block
-// (table entry pos/16 must be installed).  Context = positions 0 .. pos.  `chunk` tokens per
-// split (multiple of 128, at most 2048); with n_splits > 1 the partials go to
-// `part_o` / `part_ml` and launch_attn_merge combines them into `out`.  `step_table`
+// (table entry pos/16 must be installed).  Context = positions 0 .. pos.  Row i's own
+// work-groups cover positions t_start[i] .. pos in splits of `chunk` tokens (multiple of 128,
+// at most 2048), n_splits >= ceil((pos + 1 - t_start[i]) / chunk) for every row; positions
+// below t_start[i] are covered by the row's set.  With more than one partial slot per row
+// (n_splits + grp.n_shared > 1, at most 32) the partials go to `part_o` / `part_ml` and
+// launch_attn_merge (same chunk, n_splits, grp) combines them into `out`.  `step_table`
 // (optional, device int32 [M, step_stride]): the block ids of row i's sequence, entries
 // 0 .. pos/16 at least, laid out by launch row; replaces the lookup through st.table.
 hipError_t launch_attn_decode(hipStream_t s, const float* qkv, int M, RowMeta rm, SeqState st,
                               const f16* bq, const f16* bk, const f16* bv, const float* cos_tab,
                               const float* sin_tab, f16* arena_layer, KvGeom geom, int n_q_heads,
                               int chunk, int n_splits, float* part_o, float* part_ml, f16* out,
-                              const int32_t* step_table = nullptr, int step_stride = 0);
+                              const int32_t* step_table = nullptr, int step_stride = 0,
+                              DecodeGroups grp = DecodeGroups{});
 hipError_t launch_attn_merge(hipStream_t s, int M, RowMeta rm, int head_dim, int n_q_heads, int chunk,
-                             int n_splits, const float* part_o, const float* part_ml, f16* out);
+                             int n_splits, const float* part_o, const float* part_ml, f16* out,
+                             DecodeGroups grp = DecodeGroups{});
 hipError_t launch_attn_prefill(hipStream_t s, const f16* q, const AttnWork* work, int n_work,
                                SeqState st, const f16* arena_layer, KvGeom geom, int n_q_heads,
                                f16* out);

@@ -86,7 +86,9 @@ Layout make_layout(const areal_model_cfg& c) {
   // per pass: slot, pos, token, new_block per row + work items + last rows
   // (+ in a decode step the block ids of every row's sequence, laid out by row)
   const uint64_t per_pass = M * 16 + (M / 16 + 2 * (uint64_t)c.max_seqs + 64) * 16 + (uint64_t)c.max_seqs * 16 +
-                            (uint64_t)c.max_seqs * (L.max_blocks + 4) * 4;
+                            (uint64_t)c.max_seqs * (L.max_blocks + 4) * 4 +
+                            // decode step: t_start per row, tile rows and start per set, block ids per set
+                            (uint64_t)c.max_seqs * (4 + (kGroupTiles * 16 * 4 + 4 + (L.max_blocks + 4) * 4) / 2) + 256;
   L.ring_bytes = align_up(std::max<uint64_t>(per_pass * 2, 1u << 20), 4096) * kRingSegs;
   L.ring = take(L.ring_bytes);
   L.samp = take(sampler_scratch_bytes());
@@ -144,6 +146,13 @@ struct areal_ctx {
   std::string err;
   int split_target = 3072;              // decode attention: work-groups per launch aimed at
   int min_chunk = 256;
+  // Decode attention can walk the leading blocks that rows share once per set of rows: 1 = whenever
+  // rows share, 0 = never, -1 = when the shared part is most of what the launch reads (measured on
+  // the MI355X: 7-9 % off the attention launch where 80 % of the context tokens read are shared, a
+  // loss of 2-12 % where it is a quarter or less: the repeated reads of a block already meet in L2,
+  // and the extra partial slots cost the merge more than the rows' own walks save)
+  int group_decode = -1;
+  int64_t set_rows_sum = 0, set_row_tokens_sum = 0, set_tokens_sum = 0;
   // measurement hook
   int prof_class = -1, prof_layer = 0, prof_every = 1;
   int64_t prof_pass = 0;
@@ -307,6 +316,7 @@ struct PassArgs {
   double attn_units;              // context tokens read (decode) / query-key pairs (prefill)
   const int32_t* step_table = nullptr;   // decode: block ids by launch row (device), row stride below
   int step_stride = 0;
+  DecodeGroups groups;                   // decode: sets of rows that share leading blocks
   // scoring passes (teacher-forced log-probs of every row's next token)
   const int32_t* target = nullptr;   // device [M]: token each row predicts, -1 = none
   float inv_t = 1.f;
@@ -362,12 +372,13 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
         ProfScope ps(c, AREAL_K_ATTN_DECODE, l, sampled, a.attn_units);
         HIP_TRY(c, launch_attn_decode(s, qkv, a.M, a.rm, st, bq, bk, bv, cos_t, sin_t, arena_l, c->geom, nq,
                                       a.chunk, a.n_splits, c->wsp<float>(c->lay.part_o),
-                                      c->wsp<float>(c->lay.part_ml), attn, a.step_table, a.step_stride));
+                                      c->wsp<float>(c->lay.part_ml), attn, a.step_table, a.step_stride,
+                                      a.groups));
       }
-      if (a.n_splits > 1) {
+      if (a.n_splits + a.groups.n_shared > 1) {
         ProfScope ps(c, AREAL_K_ATTN_MERGE, l, sampled, rows);
         HIP_TRY(c, launch_attn_merge(s, a.M, a.rm, d, nq, a.chunk, a.n_splits, c->wsp<float>(c->lay.part_o),
-                                     c->wsp<float>(c->lay.part_ml), attn));
+                                     c->wsp<float>(c->lay.part_ml), attn, a.groups));
       }
     } else {
       {
@@ -568,6 +579,7 @@ int areal_create(const areal_model_cfg* cfg, areal_ctx** out) {
     const int v = atoi(e);
     if (v >= 64 && v <= 65536) c->split_target = v;
   }
+  if (const char* e = getenv("AREAL_DECODE_GROUPS")) c->group_decode = atoi(e) > 0 ? 1 : (atoi(e) == 0 ? 0 : -1);
   if (const char* e = getenv("AREAL_DECODE_MIN_CHUNK")) {
     const int v = atoi(e);
     if (v >= 128 && v <= 2048 && v % 128 == 0) c->min_chunk = v;
@@ -777,20 +789,113 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
     need_blocks += c->alloc->extra_needed(id, c->seqs[id].len + 1);
   }
   if (need_blocks > c->alloc->n_free()) return fail(c, AREAL_E_NOMEM, "KV arena exhausted");
-  // per-step block table: row i lists the blocks of seq_ids[i] (the attention kernel then finds
-  // its block ids from the launch row alone, without going through the sequence's slot)
-  int longest = 0;
-  for (int i = 0; i < n; ++i) longest = std::max(longest, c->seqs[seq_ids[i]].len + 1);
-  const int tab_stride = (c->alloc->blocks_for(longest) + 3) / 4 * 4;
-  int rc = ring_begin(c, align_up((uint64_t)n * 4, 64) * 3 + align_up((uint64_t)n * tab_stride * 4, 64));
+  // Rows whose sequences hold the same leading blocks (the samples of a prompt): rows are
+  // bucketed by their first block id, and the blocks all rows of a bucket have in common are
+  // walked once per set of up to kGroupTiles * floor(16 / G) rows instead of once per row.
+  const int P = 16 / (g.n_q_heads / g.n_kv_heads);
+  std::vector<int> t_start(n, 0);
+  struct RowSet { int start_blocks; std::vector<int> rows; };
+  std::vector<RowSet> sets;
+  int max_shared_blocks = 0;
+  if (c->group_decode != 0 && n >= 2) {
+    std::unordered_map<int32_t, std::vector<int>> by_first;
+    std::vector<int32_t> order;
+    for (int i = 0; i < n; ++i) {
+      const auto& blocks = c->alloc->blocks(seq_ids[i]);
+      if (blocks.empty()) continue;
+      auto& v = by_first[blocks[0]];
+      if (v.empty()) order.push_back(blocks[0]);
+      v.push_back(i);
+    }
+    for (int32_t first : order) {
+      const std::vector<int>& rows = by_first[first];
+      if (rows.size() < 2) continue;
+      const auto& lead = c->alloc->blocks(seq_ids[rows[0]]);
+      // shared blocks are full and precede the position every row appends at
+      int common = c->seqs[seq_ids[rows[0]]].len / AREAL_KV_BLOCK_TOKENS;
+      for (size_t k = 1; k < rows.size() && common > 0; ++k) {
+        const auto& b = c->alloc->blocks(seq_ids[rows[k]]);
+        common = std::min(common, c->seqs[seq_ids[rows[k]]].len / AREAL_KV_BLOCK_TOKENS);
+        int same = 0;
+        while (same < common && b[same] == lead[same]) ++same;
+        common = same;
+      }
+      if (common < 1) continue;
+      for (size_t k = 0; k < rows.size(); k += (size_t)kGroupTiles * P) {
+        RowSet rs{common, {}};
+        for (size_t q = k; q < std::min(rows.size(), k + (size_t)kGroupTiles * P); ++q) rs.rows.push_back(rows[q]);
+        sets.push_back(std::move(rs));
+      }
+      for (int r : rows) t_start[r] = common * AREAL_KV_BLOCK_TOKENS;
+      max_shared_blocks = std::max(max_shared_blocks, common);
+    }
+  }
+  // split the KV walk so that the grid holds a few work-groups per compute unit
+  // (targets of 768 .. 6144 work-groups and minimum splits of 128 .. 512 tokens measured within
+  // 5 % of each other on the rollout's context mixes; environment knobs AREAL_DECODE_SPLIT_TARGET
+  // and AREAL_DECODE_MIN_CHUNK, read at areal_create, repeat that sweep)
+  int64_t sum_ctx = 0;
+  int max_ctx = 0, max_own = 0;
+  for (int i = 0; i < n; ++i) {
+    const int ctx = c->seqs[seq_ids[i]].len + 1;
+    sum_ctx += ctx;
+    max_ctx = std::max(max_ctx, ctx);
+    max_own = std::max(max_own, ctx - t_start[i]);
+  }
+  if (c->group_decode < 0 && !sets.empty()) {
+    int64_t shared_sum = 0;
+    for (int i = 0; i < n; ++i) shared_sum += t_start[i];
+    if (shared_sum * 10 < sum_ctx * 7) {
+      sets.clear();
+      std::fill(t_start.begin(), t_start.end(), 0);
+      max_shared_blocks = 0;
+      max_own = max_ctx;
+    }
+  }
+  int64_t chunk = (sum_ctx * g.n_kv_heads / c->split_target + 127) / 128 * 128;
+  chunk = std::min<int64_t>(std::max<int64_t>(chunk, c->min_chunk), 2048);   // a split spans at most 128 blocks
+  int n_splits = (int)((max_own + chunk - 1) / chunk);
+  // the shared part goes in short pieces (a work-group of a set has each wave walk all blocks of
+  // its piece, so a piece is two block pairs where eight partial slots suffice, longer for longer
+  // prompts)
+  const int max_shared = max_shared_blocks * AREAL_KV_BLOCK_TOKENS;
+  int sh_chunk = std::max(64, (max_shared + 8 * 64 - 1) / (8 * 64) * 64);
+  int n_shared = max_shared ? (max_shared + sh_chunk - 1) / sh_chunk : 0;
+  if (sh_chunk > 2048 || n_splits + n_shared > kMaxSplits) {   // very deep contexts: every row walks all its blocks itself
+    sets.clear();
+    std::fill(t_start.begin(), t_start.end(), 0);
+    max_shared_blocks = 0;
+    n_shared = 0;
+    n_splits = (int)((max_ctx + chunk - 1) / chunk);
+    if (n_splits > kMaxSplits) {
+      chunk = ((max_ctx + kMaxSplits - 1) / kMaxSplits + 127) / 128 * 128;
+      n_splits = (int)((max_ctx + chunk - 1) / chunk);
+    }
+  }
+  // per-step block table: row i lists the blocks of seq_ids[i] from block t_start[i] / 16 on (the
+  // attention kernel then finds its block ids from the launch row alone, without going through
+  // the sequence's slot); row n + k lists the leading blocks of set k
+  const int n_sets = (int)sets.size();
+  int longest_blocks = max_shared_blocks;
+  for (int i = 0; i < n; ++i)
+    longest_blocks = std::max(longest_blocks, c->alloc->blocks_for(c->seqs[seq_ids[i]].len + 1) -
+                                                  t_start[i] / AREAL_KV_BLOCK_TOKENS);
+  const int tab_stride = (longest_blocks + 3) / 4 * 4;
+  const uint64_t set_rows_bytes = (uint64_t)n_sets * kGroupTiles * 16 * 4;
+  int rc = ring_begin(c, align_up((uint64_t)n * 4, 64) * 4 + align_up((uint64_t)(n + n_sets) * tab_stride * 4, 64) +
+                             align_up(set_rows_bytes, 64) + align_up((uint64_t)n_sets * 4, 64));
   if (rc) return rc;
   const uint64_t start = c->seg_used;
   Staged s_slot = ring_take(c, (uint64_t)n * 4), s_pos = ring_take(c, (uint64_t)n * 4),
-         s_nb = ring_take(c, (uint64_t)n * 4), s_tab = ring_take(c, (uint64_t)n * tab_stride * 4);
+         s_nb = ring_take(c, (uint64_t)n * 4), s_ts = ring_take(c, (uint64_t)n * 4),
+         s_tab = ring_take(c, (uint64_t)(n + n_sets) * tab_stride * 4);
+  Staged s_rows{nullptr, nullptr}, s_start{nullptr, nullptr};
+  if (n_sets) {
+    s_rows = ring_take(c, set_rows_bytes);
+    s_start = ring_take(c, (uint64_t)n_sets * 4);
+  }
   int32_t *hslot = (int32_t*)s_slot.host, *hpos = (int32_t*)s_pos.host, *hnb = (int32_t*)s_nb.host,
-          *htab = (int32_t*)s_tab.host;
-  int64_t sum_ctx = 0;
-  int max_ctx = 0;
+          *hts = (int32_t*)s_ts.host, *htab = (int32_t*)s_tab.host;
   for (int i = 0; i < n; ++i) {
     const int id = seq_ids[i];
     SeqInfo& s = c->seqs[id];
@@ -798,31 +903,32 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
     const size_t had = c->alloc->blocks(id).size();
     c->alloc->reserve(id, pos + 1);
     const auto& blocks = c->alloc->blocks(id);
+    const int skip = t_start[i] / AREAL_KV_BLOCK_TOKENS;
     hslot[i] = id;
     hpos[i] = pos;
+    hts[i] = t_start[i];
     hnb[i] = blocks.size() > had ? blocks.back() : -1;
-    memcpy(htab + (size_t)i * tab_stride, blocks.data(), blocks.size() * 4);
-    for (int b = (int)blocks.size(); b < tab_stride; ++b) htab[(size_t)i * tab_stride + b] = 0;
+    int32_t* trow = htab + (size_t)i * tab_stride;
+    memcpy(trow, blocks.data() + skip, (blocks.size() - skip) * 4);
+    for (int b = (int)blocks.size() - skip; b < tab_stride; ++b) trow[b] = 0;
     s.versions.push_back(s.pending_version);
     s.len = pos + 1;
     s.kv_len = pos + 1;
     s.pending_version = c->version;
-    sum_ctx += pos + 1;
-    max_ctx = std::max(max_ctx, pos + 1);
+  }
+  for (int k = 0; k < n_sets; ++k) {
+    const RowSet& rs = sets[k];
+    int32_t* trow = htab + (size_t)(n + k) * tab_stride;
+    const auto& lead = c->alloc->blocks(seq_ids[rs.rows[0]]);
+    memcpy(trow, lead.data(), (size_t)rs.start_blocks * 4);
+    for (int b = rs.start_blocks; b < tab_stride; ++b) trow[b] = 0;
+    int32_t* hrows = (int32_t*)s_rows.host + (size_t)k * kGroupTiles * 16;
+    for (int q = 0; q < kGroupTiles * 16; ++q) hrows[q] = -1;
+    for (size_t q = 0; q < rs.rows.size(); ++q) hrows[(q / P) * 16 + q % P] = rs.rows[q];
+    ((int32_t*)s_start.host)[k] = rs.start_blocks * AREAL_KV_BLOCK_TOKENS;
   }
   rc = ring_flush(c, start);
   if (rc) return rc;
-  // split the KV walk so that the grid holds a few work-groups per compute unit
-  // (targets of 768 .. 6144 work-groups and minimum splits of 128 .. 512 tokens measured within
-  // 5 % of each other on the rollout's context mixes; environment knobs AREAL_DECODE_SPLIT_TARGET
-  // and AREAL_DECODE_MIN_CHUNK, read at areal_create, repeat that sweep)
-  int64_t chunk = (sum_ctx * g.n_kv_heads / c->split_target + 127) / 128 * 128;
-  chunk = std::min<int64_t>(std::max<int64_t>(chunk, c->min_chunk), 2048);   // a split spans at most 128 blocks
-  int n_splits = (int)((max_ctx + chunk - 1) / chunk);
-  if (n_splits > kMaxSplits) {
-    chunk = ((max_ctx + kMaxSplits - 1) / kMaxSplits + 127) / 128 * 128;
-    n_splits = (int)((max_ctx + chunk - 1) / chunk);
-  }
   PassArgs a{};
   a.M = n;
   a.rm = RowMeta{(const int32_t*)s_slot.dev, (const int32_t*)s_pos.dev};
@@ -837,6 +943,19 @@ int areal_decode_step(areal_ctx* c, int32_t n, const int32_t* seq_ids, const int
   a.attn_units = (double)sum_ctx;
   a.step_table = (const int32_t*)s_tab.dev;
   a.step_stride = tab_stride;
+  for (const RowSet& rs : sets) {
+    c->set_rows_sum += (int64_t)rs.rows.size();
+    c->set_row_tokens_sum += (int64_t)rs.rows.size() * rs.start_blocks * AREAL_KV_BLOCK_TOKENS;
+    c->set_tokens_sum += (int64_t)rs.start_blocks * AREAL_KV_BLOCK_TOKENS;
+  }
+  if (n_sets) {
+    a.groups.t_start = (const int32_t*)s_ts.dev;
+    a.groups.set_rows = (const int32_t*)s_rows.dev;
+    a.groups.set_start = (const int32_t*)s_start.dev;
+    a.groups.n_sets = n_sets;
+    a.groups.sh_chunk = sh_chunk;
+    a.groups.n_shared = n_shared;
+  }
   return run_pass(c, a);
 }
 
@@ -1058,6 +1177,14 @@ int areal_kv_blocks(areal_ctx* c, int64_t* total, int64_t* free_) {
   if (!c) return AREAL_E_INVAL;
   if (total) *total = c->alloc->n_blocks();
   if (free_) *free_ = c->alloc->n_free();
+  return AREAL_OK;
+}
+
+int areal_decode_set_counters(areal_ctx* c, int64_t* rows, int64_t* row_tokens, int64_t* set_tokens) {
+  if (!c) return AREAL_E_INVAL;
+  if (rows) *rows = c->set_rows_sum;
+  if (row_tokens) *row_tokens = c->set_row_tokens_sum;
+  if (set_tokens) *set_tokens = c->set_tokens_sum;
   return AREAL_OK;
 }
 

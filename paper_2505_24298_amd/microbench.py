@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Single-kernel microbenchmarks on the MI355X (tuning and profiling aids).
 
-  python3 paper_2505_24298_amd/microbench.py attn-decode [shared]
+  python3 paper_2505_24298_amd/microbench.py attn-decode [shared [steps,...]]
       decode steps at the context mixes the qwen2-1.5b-rollout workload has after
       500 / 1500 / 3000 / 5000 / 7000 generated tokens (sequences adopted at those
       lengths, K/V pool filled with N(0,1)); reports the decode-attention launch
@@ -44,14 +44,14 @@ def _weights(torch, cfg):
     return device_weights(torch, cfg, 0, "cuda:0")
 
 
-def attn_decode(shared=False):
+def attn_decode(shared=False, steps=(500, 1500, 3000, 5000, 7000)):
     import torch
     from paper_2505_24298_amd import binding, synth
     cfg, wl, prompts, outs = synth.make_workload("qwen2-1.5b-rollout")
     w = _weights(torch, cfg)
     kvb = 2 * cfg["n_kv_heads"] * cfg["head_dim"] * 2
     group = wl["samples"]
-    for step in (500, 1500, 3000, 5000, 7000):
+    for step in steps:
         live = [i for i, o in enumerate(outs) if o > step]
         lens = [len(prompts[i]) + step for i in live]
         B = len(lens)
@@ -263,7 +263,10 @@ def score():
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else ""
     if what == "attn-decode":
-        attn_decode(shared=len(sys.argv) > 2 and sys.argv[2] == "shared")
+        if len(sys.argv) > 3:
+            attn_decode(shared=sys.argv[2] == "shared", steps=tuple(int(x) for x in sys.argv[3].split(",")))
+        else:
+            attn_decode(shared=len(sys.argv) > 2 and sys.argv[2] == "shared")
     elif what == "copy":
         copy_calibration()
     elif what == "gemm-chosen":
