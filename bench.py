@@ -74,6 +74,49 @@ def measured_copy_bandwidth(torch, dev, gib=2, reps=5):
     return 2.0 * n / (ms * 1e-3) / 1e9
 
 
+def measured_read_bandwidth(torch, binding, dev, sizes_mb=(32, 64, 128, 256, 512), reps=12):
+    """What a kernel that only reads reaches on this machine, per launch size: [(bytes, GB/s)], each launch
+    between its own pair of events (as the library brackets the attention launch), over a 2 GiB buffer
+    walked in order so that no launch finds its bytes in a cache."""
+    total = 2 << 30
+    buf = torch.empty(total, dtype=torch.uint8, device=dev)
+    buf.view(torch.int32).random_()
+    sink = torch.zeros(16, dtype=torch.uint8, device=dev)
+    out = []
+    off = 0
+    for mb in sizes_mb:
+        n = mb << 20
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            if off + n > total:
+                off = 0
+            a.record()
+            binding.op_stream_read(buf, off, n, sink)
+            b.record()
+            off += n
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev[2:])
+        out.append((n, n / (sum(ms) / len(ms) * 1e-3) / 1e9))
+    del buf
+    torch.cuda.empty_cache()
+    return out
+
+
+def read_bandwidth_at(curve, nbytes):
+    """GB/s of a plain read of nbytes, interpolated (in launch time) between the measured sizes."""
+    pts = [(b, b / (g * 1e9)) for b, g in curve]                 # (bytes, seconds)
+    if nbytes <= pts[0][0]:
+        t = pts[0][1] * nbytes / pts[0][0]
+    elif nbytes >= pts[-1][0]:
+        t = pts[-1][1] * nbytes / pts[-1][0]
+    else:
+        for (b0, t0), (b1, t1) in zip(pts, pts[1:]):
+            if b0 <= nbytes <= b1:
+                t = t0 + (t1 - t0) * (nbytes - b0) / (b1 - b0)
+                break
+    return nbytes / t / 1e9
+
+
 def cpu_oracle_baseline(cfg_name, host_weights, budget_s=20.0):
     """The CPU oracle as it stands (incremental-KV variant, numpy float64) on a
     bounded slice of the same workload: 4 sequences of the workload's model
@@ -208,7 +251,7 @@ def streaming(args):
     print(json.dumps(out))
 
 
-def summarise(args, cfg, wl, n, runs, warmups_done, copy_gbs, cpu_baseline, binding):
+def summarise(args, cfg, wl, n, runs, warmups_done, copy_gbs, cpu_baseline, binding, read_curve=None):
     """The JSON line for the timed rollouts in `runs`."""
     steps = len(runs)
     total_s = sum(r["total_ms"] for r in runs) / 1e3
@@ -239,6 +282,13 @@ def summarise(args, cfg, wl, n, runs, warmups_done, copy_gbs, cpu_baseline, bind
                         distinct_kv_bytes_per_launch=int(distinct_per_launch),
                         launches_timed=int(pn), avg_launch_us=round(pms / pn * 1e3, 2),
                         avg_context_tokens_per_launch=round(punits / pn, 1))
+        if read_curve:
+            # the same bytes through a kernel that only reads them, bracketed the same way
+            rd = read_bandwidth_at(read_curve, roofline["traffic"])
+            roofline["plain_read_GBps_at_traffic"] = round(rd, 1)
+            roofline["launch_time_of_plain_read_over_kernel"] = round(
+                (roofline["traffic"] / (rd * 1e9)) / (pms / pn * 1e-3), 4)
+            roofline["plain_read_curve"] = [[int(b), round(g, 1)] for b, g in read_curve]
     else:
         roofline = dict(bound="hbm", kernel=f"class {args.profile_class}", achieved=None, peak=HBM_PEAK_GBS,
                         unit="GB/s", frac=None, traffic=None, launches_timed=int(pn),
@@ -358,6 +408,8 @@ def main():
         log(f"cpu oracle: {cpu_baseline['value']} tokens/s")
     copy_gbs = measured_copy_bandwidth(torch, dev)
     log(f"device copy: {copy_gbs:.0f} GB/s read+write")
+    read_curve = measured_read_bandwidth(torch, binding, dev)
+    log("plain read: " + ", ".join(f"{b >> 20} MiB {g:.0f} GB/s" for b, g in read_curve))
 
     eng = binding.Areal(cfg, max_seqs=n, max_seq_len=max_len, max_batch_tokens=args.max_batch_tokens,
                         kv_blocks=kv_blocks)
@@ -372,8 +424,8 @@ def main():
         if state["printed"] or not runs:
             return
         state["printed"] = True
-        print(json.dumps(summarise(args, cfg, wl, n, runs, warmups_done, copy_gbs, cpu_baseline, binding)),
-              flush=True)
+        print(json.dumps(summarise(args, cfg, wl, n, runs, warmups_done, copy_gbs, cpu_baseline, binding,
+                                   read_curve)), flush=True)
 
     def on_term(signum, frame):
         log(f"signal {signum}: reporting the {len(runs)} rollouts completed")

@@ -31,6 +31,15 @@ int areal_op_gemm_num_configs(void);
 int areal_op_gemm_choose(int32_t M, int32_t N, int32_t K, int32_t mode, int32_t* cfg_out,
                          int32_t* splits_out);
 
+/* Calibration for the roofline of the streaming kernels (Section 3.2: decoding is
+ * memory-IO bound): a kernel that reads `bytes` (multiple of 16, device, 16-byte
+ * aligned) from `src` and does nothing else, launched like the decode kernels
+ * (one work-group per 64 KiB).  Timed by the caller, it says what bandwidth a
+ * read of that size reaches on this device, ramp-up of the launch included.
+ * `sink16`: 16 bytes of device memory that may be written.
+ * Returns 0 or AREAL_E_INVAL / AREAL_E_HIP (message: areal_last_error(NULL)). */
+int areal_op_stream_read(void* hip_stream, const void* src, uint64_t bytes, void* sink16);
+
 #ifdef __cplusplus
 }
 #endif

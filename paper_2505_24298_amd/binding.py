@@ -96,6 +96,7 @@ _SIGNATURES = {
                                 C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "areal_op_gemm_num_configs": (C.c_int, []),
     "areal_op_gemm_choose": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _I32P, _I32P]),
+    "areal_op_stream_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     # include/areal_host.h
     "areal_kvalloc_create": (C.c_void_p, [C.c_int64, C.c_int32, C.c_int32]),
     "areal_kvalloc_destroy": (None, [C.c_void_p]),
@@ -419,6 +420,16 @@ def op_gemm(A, W0, W1, C_out, mode, cfg=-1, splits=-1):
                              None if W1 is None else W1.data_ptr(), C_out.data_ptr(), M, N, K, mode, cfg, splits)
     if rc != OK:
         raise ArealError(rc, "areal_op_gemm")
+
+
+def op_stream_read(buf, offset, nbytes, sink):
+    """areal_op_stream_read over bytes [offset, offset + nbytes) of the torch uint8 tensor `buf`
+    (current stream); `sink`: a device tensor of at least 16 bytes."""
+    import torch
+    rc = lib().areal_op_stream_read(torch.cuda.current_stream().cuda_stream, buf.data_ptr() + int(offset),
+                                    int(nbytes), sink.data_ptr())
+    if rc != OK:
+        raise ArealError(rc, lib().areal_last_error(None).decode())
 
 
 def weights_to_device(w, device="cuda:0", bf16=True, f16=False):

@@ -225,6 +225,37 @@ hipError_t launch_stage_copy(hipStream_t s, const void* src_host_mapped, void* d
   return hipGetLastError();
 }
 
+// Calibration: a read of `n16` 16-byte words that does nothing else (one work-group per 64 KiB,
+// eight loads in flight per lane), the yardstick for the kernels that stream K/V or weights.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, int64_t n16,
+                                                          uint32_t never, u32x4* __restrict__ sink) {
+  constexpr int PER_WG = 4096;                        // 16-byte words per work-group
+  const int64_t w0 = (int64_t)blockIdx.x * PER_WG;
+  u32x4 acc = {0, 0, 0, 0};
+  for (int q = 0; q < PER_WG; q += 256 * 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int64_t i = w0 + q + u * 256 + threadIdx.x;
+      v[u] = i < n16 ? src[i] : u32x4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  // `never` is a value the xor of the data does not take (the caller's choice): keeps the loads alive
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == never && never != 0) *sink = acc;
+}
+
+hipError_t launch_stream_read(hipStream_t s, const void* src, size_t bytes, uint32_t never, void* sink16) {
+  if (!src || !sink16 || bytes == 0 || bytes % 16 || ((uintptr_t)src & 15) || ((uintptr_t)sink16 & 15) ||
+      bytes > (size_t)1 << 36)
+    return hipErrorInvalidValue;
+  const int64_t n16 = (int64_t)(bytes / 16);
+  stream_read_kernel<<<(unsigned)((n16 + 4095) / 4096), 256, 0, s>>>(reinterpret_cast<const u32x4*>(src), n16, never,
+                                                                       reinterpret_cast<u32x4*>(sink16));
+  return hipGetLastError();
+}
+
 // Parameter sets arrive as float32 or bf16 and are held as halves for the
 // matrix cores (round to nearest even; bf16 values with |w| >= 2^-14 convert
 // exactly).  Magnitudes beyond the half range saturate to +-65504.

@@ -241,6 +241,48 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const f16* __restric
 }
 
 
+// Epilogue of the direct-to-LDS kernels: the wave's accumulators to C.
+template <int BM, int BN, int WM, int WN, int MODE>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[BM / WM / 32][BN / WN / 32], void* __restrict__ Cv,
+                                           int M, int N, int ldc, int tile_m, int tile_n, int wm, int wn,
+                                           int fr, int fh, int atomic) {
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  const int m0 = tile_m * BM;
+  if (MODE == GEMM_SWIGLU_F16) {
+    f16* C = reinterpret_cast<f16*>(Cv);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; j += 2) {
+        const int f = tile_n * (BN / 2) + (wn * (BN / WN) + j * 32) / 2 + fr;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+          if (m < M && f < N)
+            C[(int64_t)m * ldc + f] = f2h_sat(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
+        }
+      }
+  } else {
+    float* C = reinterpret_cast<float*>(Cv);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = tile_n * BN + wn * (BN / WN) + j * 32 + fr;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+          if (m < M && n < N) {
+            float* p = C + (int64_t)m * ldc + n;
+            if (atomic) unsafeAtomicAdd(p, acc[i][j][v]);
+            else if (MODE == GEMM_ADD_F32) *p += acc[i][j][v];
+            else *p = acc[i][j][v];
+          }
+        }
+      }
+  }
+}
+
 // ---- direct-to-LDS variant ---------------------------------------------------
 // Same tiling, but the K-slabs travel HBM -> LDS with global_load_lds_dwordx4
 // (no register staging) into a ring of STAGES slab buffers, so STAGES-1 slabs
@@ -385,39 +427,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
   }
   // (all remaining in-flight loads target LDS only; the epilogue does not touch LDS)
 
-  if (MODE == GEMM_SWIGLU_F16) {
-    f16* C = reinterpret_cast<f16*>(Cv);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; j += 2) {
-        const int f = tile_n * (BN / 2) + (wn * (BN / WN) + j * 32) / 2 + fr;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
-          if (m < M && f < N)
-            C[(int64_t)m * ldc + f] = f2h_sat(silu_f(acc[i][j][v]) * acc[i][j + 1][v]);
-        }
-      }
-  } else {
-    float* C = reinterpret_cast<float*>(Cv);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = tile_n * BN + wn * (BN / WN) + j * 32 + fr;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
-          if (m < M && n < N) {
-            float* p = C + (int64_t)m * ldc + n;
-            if (atomic) unsafeAtomicAdd(p, acc[i][j][v]);
-            else if (MODE == GEMM_ADD_F32) *p += acc[i][j][v];
-            else *p = acc[i][j][v];
-          }
-        }
-      }
-  }
+  store_tile<BM, BN, WM, WN, MODE>(acc, Cv, M, N, ldc, tile_m, tile_n, wm, wn, fr, fh, atomic);
   // drain the loads that were requested past the end before the LDS is released
   wait_vmcnt(0);
 }

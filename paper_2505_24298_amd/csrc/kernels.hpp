@@ -39,6 +39,9 @@ hipError_t launch_append(hipStream_t s, int n, int vocab, RowMeta rm, const int3
 hipError_t launch_table_patch(hipStream_t s, const int32_t* patch, int n, SeqState st);
 hipError_t launch_hist_copy(hipStream_t s, const int32_t* jobs, int n, SeqState st);
 hipError_t launch_stage_copy(hipStream_t s, const void* src_host_mapped, void* dst, size_t bytes);
+// reads `bytes` (multiple of 16) and discards them; *sink16 (16 bytes) is written only if the xor of all
+// words read equals `never` (pass any value: a write there is harmless)
+hipError_t launch_stream_read(hipStream_t s, const void* src, size_t bytes, uint32_t never, void* sink16);
 hipError_t launch_to_f16(hipStream_t s, const void* src, int src_is_bf16, f16* dst, int64_t n);
 
 // ---- gemm.hip ---------------------------------------------------------------

@@ -1282,4 +1282,18 @@ int areal_op_gemm_choose(int32_t M, int32_t N, int32_t K, int32_t mode, int32_t*
   return AREAL_OK;
 }
 
+int areal_op_stream_read(void* hip_stream, const void* src, uint64_t bytes, void* sink16) {
+  if (!src || !sink16 || bytes == 0 || bytes % 16) {
+    set_global_error("areal_op_stream_read: NULL pointer, or a size that is not a positive multiple of 16");
+    return AREAL_E_INVAL;
+  }
+  const hipError_t e = launch_stream_read(reinterpret_cast<hipStream_t>(hip_stream), src, (size_t)bytes,
+                                          0x5bd1e995u, sink16);
+  if (e != hipSuccess) {
+    set_global_error(std::string("areal_op_stream_read: ") + hipGetErrorString(e));
+    return e == hipErrorInvalidValue ? AREAL_E_INVAL : AREAL_E_HIP;
+  }
+  return AREAL_OK;
+}
+
 }  // extern "C"

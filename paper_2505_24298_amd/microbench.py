@@ -9,14 +9,19 @@
       `shared` the samples of a prompt hold the prompt's KV blocks together, as after
       areal_prefill of the workload (16 samples per prompt), and the line also gives
       the distinct context tokens per launch.
-  python3 paper_2505_24298_amd/microbench.py gemm-chosen [M,M,...] [shape,...]
+  python3 paper_2505_24298_amd/microbench.py gemm-chosen [M,M,...] [shape,...] [working set in MB]
       the projection GEMMs at the library's own tile choice only (a short run for
       rocprofv3 --pmc: bytes fetched against weight bytes, matrix-core busy cycles).
+      The weights rotate over 1.2 GB (every launch reads them from HBM) or over the
+      given working set (150: they sit in the 256 MB memory-side cache, in no L2).
   python3 paper_2505_24298_amd/microbench.py gemm [M,M,...] [shape,...]
       every tile configuration x K split of the projection GEMM at the decoder's
       shapes (qkv, o, gateup, down, lmhead of the 1.5B shape; qkv7 ... lmhead7 of the 7B shape);
       weights rotate over
       > 1 GB so they come from HBM.
+  python3 paper_2505_24298_amd/microbench.py read
+      what a kernel that only reads reaches per launch size (32 MiB .. 1 GiB), each launch
+      between its own pair of events: the yardstick for the decode attention launch.
   python3 paper_2505_24298_amd/microbench.py copy
       four plain 1 GiB device-to-device copies: the calibration of the FETCH_SIZE /
       WRITE_SIZE counters (known bytes per dispatch).
@@ -92,6 +97,30 @@ def attn_decode(shared=False, steps=(500, 1500, 3000, 5000, 7000)):
         del eng
 
 
+def read_calibration():
+    import torch
+    from paper_2505_24298_amd import binding
+    total = 3 << 30
+    buf = torch.empty(total, dtype=torch.uint8, device="cuda")
+    buf.view(torch.int32).random_()
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    off = 0
+    for mb in (32, 64, 128, 192, 256, 512, 1024):
+        n = mb << 20
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(14)]
+        for a, b in ev:
+            if off + n > total:
+                off = 0
+            a.record()
+            binding.op_stream_read(buf, off, n, sink)
+            b.record()
+            off += n
+        torch.cuda.synchronize()
+        us = [a.elapsed_time(b) * 1e3 for a, b in ev[2:]]
+        print(json.dumps(dict(read_MiB=mb, launches=len(us), us=round(sum(us) / len(us), 2),
+                              GBps=round(n / (sum(us) / len(us) * 1e-6) / 1e9, 1))), flush=True)
+
+
 def copy_calibration():
     import torch
     a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
@@ -106,14 +135,16 @@ def copy_calibration():
     print(json.dumps(dict(copies=4, bytes_each=1 << 30, GBps_read_plus_write=round(3 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1))))
 
 
-def gemm_chosen(ms_arg, shapes_arg, iters=20):
+def gemm_chosen(ms_arg, shapes_arg, iters=20, working_set=1.2e9):
     import torch
     from paper_2505_24298_amd import binding
     g = torch.Generator(device="cuda").manual_seed(0)
     for name in shapes_arg.split(","):
         N, K, mode = GEMM_SHAPES[name]
         wbytes = N * K * 2 * (2 if mode == 2 else 1)
-        ncopy = max(2, min(64, int(1.2e9 // wbytes)))
+        # weights rotate over `working_set` bytes: > 1 GB = every launch reads them from HBM; 150 MB = they
+        # were read a few launches ago and sit in the memory-side cache (256 MB) but in no L2 (8 x 4 MB)
+        ncopy = max(2, min(64, int(working_set // wbytes)))
         mk = lambda: (torch.randn((N, K), generator=g, device="cuda") * 0.02).to(torch.float16)
         Ws = [mk() for _ in range(ncopy)]
         W1s = [mk() for _ in range(ncopy)] if mode == 2 else None
@@ -269,9 +300,12 @@ if __name__ == "__main__":
             attn_decode(shared=len(sys.argv) > 2 and sys.argv[2] == "shared")
     elif what == "copy":
         copy_calibration()
+    elif what == "read":
+        read_calibration()
     elif what == "gemm-chosen":
         gemm_chosen(sys.argv[2] if len(sys.argv) > 2 else "24,100,256",
-                    sys.argv[3] if len(sys.argv) > 3 else "qkv,o,gateup,down,lmhead")
+                    sys.argv[3] if len(sys.argv) > 3 else "qkv,o,gateup,down,lmhead",
+                    working_set=float(sys.argv[4]) * 1e6 if len(sys.argv) > 4 else 1.2e9)
     elif what == "gemm":
         gemm(sys.argv[2] if len(sys.argv) > 2 else "32,64,128,256",
              sys.argv[3] if len(sys.argv) > 3 else "qkv,o,gateup,down,lmhead")

@@ -48,3 +48,22 @@ def test_gemm_all_configs(M, N, K):
         want = ref0 / (1.0 + np.exp(-ref0)) * ref1
         got = Cb.float().cpu().numpy()
         assert np.abs(got - want).max() <= 2 ** -10 * np.abs(want).max() + 1e-6, cfg
+
+
+def test_stream_read_calibration_launch():
+    """The read-only calibration kernel: runs over whole and ragged sizes without touching anything
+    (the sink stays as it was), and refuses sizes that are not a multiple of 16 bytes."""
+    import torch
+    from paper_2505_24298_amd import binding
+    buf = torch.empty(3 << 20, dtype=torch.uint8, device="cuda")
+    buf.view(torch.int32).random_()
+    keep = buf.clone()
+    sink = torch.full((16,), 7, dtype=torch.uint8, device="cuda")
+    for off, n in ((0, 3 << 20), (4096, 65536 + 16), (16, 48), (0, 16)):
+        binding.op_stream_read(buf, off, n, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, keep) and bool((sink == 7).all())
+    with pytest.raises(binding.ArealError):
+        binding.op_stream_read(buf, 0, 40, sink)
+    with pytest.raises(binding.ArealError):
+        binding.op_stream_read(buf, 0, 0, sink)
