@@ -251,8 +251,10 @@ int areal_append_tokens(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
  *   logp_out[cu[i] + t] = log softmax(logits(x_0..x_{t-1}) / T)[x_t],  t >= 1,
  *   logp_out[cu[i]]     = 0.
  * One causal forward over all tokens (the prefill kernels, chunks of
- * max_batch_tokens rows); the output projection and the log-sum-exp run over
- * scratch_rows rows at a time, so logits for all tokens never exist at once.
+ * max_batch_tokens rows).  No logits are stored: the output projection leaves a
+ * (max, sum of exponentials) pair per row and 256-column tile in the scratch and a
+ * second kernel folds them (when the hidden size is not a multiple of 64 the
+ * logits of scratch_rows rows at a time are written there and reduced instead).
  * Live sequences are untouched: the pass borrows unused sequence slots and free
  * KV blocks and returns them before it returns (AREAL_E_NOMEM, nothing
  * queued, if there is no free slot or one sequence alone does not fit the free

@@ -283,6 +283,66 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[BM / WM / 32][BN 
   }
 }
 
+constexpr int GEMM_LSE = 3;     // internal mode of the direct-to-LDS kernel: launch_gemm_lse
+
+__device__ __forceinline__ void lse_pair_combine(float& m, float& s, float m2, float s2) {
+  const float mn = fmaxf(m, m2);
+  const float mu = mn == -INFINITY ? 0.f : mn;
+  s = s * __expf(m - mu) + s2 * __expf(m2 - mu);
+  m = mn;
+}
+
+// Epilogue of launch_gemm_lse: nothing of the tile is stored but, per row, the (max, sum of
+// exponentials) pair over the tile's columns and the value at the row's target column.  The
+// ring's LDS is reused (all its loads have landed and all waves are past their last read).
+template <int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void store_tile_lse(const f32x16 (&acc)[BM / WM / 32][BN / WN / 32], char* lds,
+                                               float2* __restrict__ part, int ld_rows, int M, int N, int tile_m,
+                                               int tile_n, int wm, int wn, int fr, int fh, const GemmLse& lse) {
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NT = WM * WN * 64;
+  float2* red = reinterpret_cast<float2*>(lds);                       // [BM][WN]
+  int32_t* tgt = reinterpret_cast<int32_t*>(lds + BM * WN * 8);       // [BM]
+  const int m0 = tile_m * BM;
+  wait_vmcnt(0);
+  __syncthreads();
+  for (int r = threadIdx.x; r < BM; r += NT) tgt[r] = m0 + r < M ? lse.target[m0 + r] : -1;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int rl = wm * (BM / WM) + i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+      const int t = tgt[rl];
+      float z[TN], m = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = tile_n * BN + wn * (BN / WN) + j * 32 + fr;
+        z[j] = n < N ? acc[i][j][v] * lse.inv_t : -INFINITY;
+        if (n == t) lse.target_z[m0 + rl] = z[j];
+        m = fmaxf(m, z[j]);
+      }
+      // the row's maximum over the wave's columns first (lanes of equal fh hold one row), then the
+      // exponentials once, against that maximum
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+      const float mu = m == -INFINITY ? 0.f : m;
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) sum += __expf(z[j] - mu);
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) sum += __shfl_xor(sum, o);
+      if (fr == 0) red[rl * WN + wn] = float2{m, sum};
+    }
+  __syncthreads();
+  for (int r = threadIdx.x; r < BM; r += NT) {
+    if (m0 + r >= M) continue;
+    float m = -INFINITY, sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < WN; ++w) lse_pair_combine(m, sum, red[r * WN + w].x, red[r * WN + w].y);
+    part[(int64_t)tile_n * ld_rows + m0 + r] = float2{m, sum};
+  }
+}
+
 // ---- direct-to-LDS variant ---------------------------------------------------
 // Same tiling, but the K-slabs travel HBM -> LDS with global_load_lds_dwordx4
 // (no register staging) into a ring of STAGES slab buffers, so STAGES-1 slabs
@@ -298,7 +358,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
                                                                 void* __restrict__ Cv, int M, int N,
                                                                 int K, int ldc, int m_tiles,
                                                                 int n_tiles, int slabs_per_split,
-                                                                int atomic) {
+                                                                int atomic, GemmLse lse) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int GA = BM / 8, GB = BN / 8;              // row groups per slab
@@ -427,14 +487,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_dma_kernel(const f16* __res
   }
   // (all remaining in-flight loads target LDS only; the epilogue does not touch LDS)
 
-  store_tile<BM, BN, WM, WN, MODE>(acc, Cv, M, N, ldc, tile_m, tile_n, wm, wn, fr, fh, atomic);
+  if constexpr (MODE == GEMM_LSE)
+    store_tile_lse<BM, BN, WM, WN>(acc, lds, reinterpret_cast<float2*>(Cv), ldc, M, N, tile_m, tile_n, wm, wn, fr,
+                                   fh, lse);
+  else
+    store_tile<BM, BN, WM, WN, MODE>(acc, Cv, M, N, ldc, tile_m, tile_n, wm, wn, fr, fh, atomic);
   // drain the loads that were requested past the end before the LDS is released
   wait_vmcnt(0);
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES, int MODE>
 hipError_t run_dma(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, int N, int K, int ldc,
-                   int splits) {
+                   int splits, GemmLse lse = GemmLse{nullptr, nullptr, 1.f}) {
   if (K % BK) return hipErrorInvalidValue;
   constexpr int n_out_per_tile = MODE == GEMM_SWIGLU_F16 ? BN / 2 : BN;
   const int n_tiles = (N + n_out_per_tile - 1) / n_out_per_tile, m_tiles = (M + BM - 1) / BM;
@@ -444,7 +508,7 @@ hipError_t run_dma(hipStream_t s, const f16* A, const GemmW& W, void* C, int M, 
   splits = (nk + sps - 1) / sps;
   const int grid = grid_blocks(m_tiles, n_tiles, splits);
   gemm_dma_kernel<BM, BN, WM, WN, STAGES, MODE><<<grid, WM * WN * 64, 0, s>>>(
-      A, W, C, M, N, K, ldc, m_tiles, n_tiles, sps, (splits > 1 || MODE == GEMM_ADD_F32) ? 1 : 0);
+      A, W, C, M, N, K, ldc, m_tiles, n_tiles, sps, (splits > 1 || MODE == GEMM_ADD_F32) ? 1 : 0, lse);
   return hipGetLastError();
 }
 
@@ -628,6 +692,19 @@ hipError_t launch_gemm_cfg(hipStream_t s, const f16* A, GemmW W, void* C, int M,
       return dispatch<GEMM_SWIGLU_F16>(s, cfg, A, W, C, M, N, K, ldc, 1);
   }
   return hipErrorInvalidValue;
+}
+
+// Column tiles of launch_gemm_lse: 256 wide above 256 rows (the 256 x 256 tile), else 128.
+int gemm_lse_tiles(int M, int N) { return M > 256 ? (N + 255) / 256 : (N + 127) / 128; }
+
+hipError_t launch_gemm_lse(hipStream_t s, const f16* A, GemmW W, int M, int N, int K, void* part, int ld_rows,
+                           GemmLse lse) {
+  if (M <= 0 || N <= 0 || K <= 0 || K % BK || ld_rows < M || !A || !part || !W.ptr[0] || W.end[0] != N ||
+      !lse.target || !lse.target_z || !(lse.inv_t > 0.f) ||
+      (((uintptr_t)A | (uintptr_t)W.ptr[0]) & 15) || ((uintptr_t)part & 7))
+    return hipErrorInvalidValue;
+  if (M > 256) return run_dma<256, 256, 2, 4, 2, GEMM_LSE>(s, A, W, part, M, N, K, ld_rows, 1, lse);
+  return run_dma<128, 128, 4, 2, 3, GEMM_LSE>(s, A, W, part, M, N, K, ld_rows, 1, lse);
 }
 
 hipError_t launch_gemm(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,

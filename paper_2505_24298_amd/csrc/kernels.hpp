@@ -56,6 +56,18 @@ enum GemmMode {
   GEMM_ADD_F32 = 1,            // C float32 += acc            (residual update)
   GEMM_SWIGLU_F16 = 2,        // two W of [N,K] (gate, up): C half = silu(A gate^T) * (A up^T)
 };
+// The output projection of a scoring pass without its [M, N] result: per row and column tile the
+// pair (max, sum of exponentials relative to it) of z = (A W^T) * inv_t, and z at the row's target
+// column.  part: float2 [n_tiles][ld_rows] (n_tiles = gemm_lse_tiles(M, N)); target: [M], -1 = none;
+// target_z: [M], written for rows whose target is in [0, N).  Requires K % 64 == 0.
+struct GemmLse {
+  const int32_t* target;
+  float* target_z;
+  float inv_t;
+};
+int gemm_lse_tiles(int M, int N);
+hipError_t launch_gemm_lse(hipStream_t s, const f16* A, GemmW W, int M, int N, int K, void* part, int ld_rows,
+                           GemmLse lse);
 hipError_t launch_gemm(hipStream_t s, const f16* A, GemmW W, void* C, int M, int N, int K, int ldc,
                        GemmMode mode);
 // Same with an explicit tile configuration (0 .. gemm_num_configs()-1) and K
@@ -125,6 +137,10 @@ void set_global_error(const std::string& msg);
 // Row r with target[r] >= 0: out[r + 1] = log softmax(logits[r] * inv_t)[target[r]];
 // rows with pos[r] == 0 also set out[r] = 0.  (Rows are consecutive tokens of
 // packed sequences: row r predicts the token stored at r + 1.)
+// out[r + 1] = target_z[r] - log sum exp over the row, from the per-tile pairs of launch_gemm_lse
+// (rows with target[r] < 0 are skipped; out[r] = 0 where pos[r] == 0)
+hipError_t launch_lse_finish(hipStream_t s, const void* part, int ld_rows, int n_tiles, const float* target_z,
+                             const int32_t* target, const int32_t* pos, int n, float* out);
 hipError_t launch_token_logprob(hipStream_t s, const float* logits, int n, int vocab, float inv_t,
                                 const int32_t* target, const int32_t* pos, float* out);
 

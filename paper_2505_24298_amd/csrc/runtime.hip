@@ -153,6 +153,7 @@ struct areal_ctx {
   // and the extra partial slots cost the merge more than the rows' own walks save)
   int group_decode = -1;
   int64_t set_rows_sum = 0, set_row_tokens_sum = 0, set_tokens_sum = 0;
+  bool fused_scoring = true;            // scoring passes fold the log-sum-exp into the output projection
   // measurement hook
   int prof_class = -1, prof_layer = 0, prof_every = 1;
   int64_t prof_pass = 0;
@@ -406,19 +407,43 @@ int run_pass(areal_ctx* c, const PassArgs& a) {
     }
   }
   if (a.target) {
-    // every row feeds the output projection, scratch_rows rows at a time: the
-    // [M, vocab] logits never exist as a whole
     HIP_TRY(c, launch_rmsnorm(s, h, w.final_norm, xn, a.M, H, g.rms_eps, nullptr));
     GemmW wl{{w.lm_head, nullptr, nullptr}, {g.vocab, 0, 0}};
-    for (int r0 = 0; r0 < a.M; r0 += a.scratch_rows) {
-      const int rows_now = std::min(a.scratch_rows, a.M - r0);
-      {
-        ProfScope ps(c, AREAL_K_GEMM_LMHEAD, -1, sampled, (double)rows_now);
-        HIP_TRY(c, launch_gemm(s, xn + (int64_t)r0 * H, wl, a.scratch, rows_now, g.vocab, H, g.vocab,
-                               GEMM_STORE_F32));
+    if (c->fused_scoring && H % 64 == 0) {
+      // Fused: the output projection keeps no logits at all, only a (max, sum of exponentials)
+      // pair per row and column tile and the value at the row's target column, all inside the
+      // caller's scratch; as many rows per launch as their pairs fit there.
+      const int64_t floats = (int64_t)a.scratch_rows * g.vocab;
+      auto cap = [&](int bn) { return floats / (2 * (int64_t)((g.vocab + bn - 1) / bn) + 1); };
+      for (int r0 = 0; r0 < a.M;) {
+        const int remaining = a.M - r0;
+        int rows_now;
+        if (remaining > 256 && cap(256) >= 512) rows_now = (int)std::min<int64_t>(remaining, cap(256));
+        else rows_now = (int)std::min<int64_t>(std::min(remaining, 256), cap(128));
+        const int n_tiles = gemm_lse_tiles(rows_now, g.vocab);
+        float* tz = a.scratch + (int64_t)2 * n_tiles * rows_now;
+        {
+          ProfScope ps(c, AREAL_K_GEMM_LMHEAD, -1, sampled, (double)rows_now);
+          HIP_TRY(c, launch_gemm_lse(s, xn + (int64_t)r0 * H, wl, rows_now, g.vocab, H, a.scratch, rows_now,
+                                     GemmLse{a.target + r0, tz, a.inv_t}));
+        }
+        HIP_TRY(c, launch_lse_finish(s, a.scratch, rows_now, n_tiles, tz, a.target + r0, a.rm.pos + r0, rows_now,
+                                     a.logp + r0));
+        r0 += rows_now;
       }
-      HIP_TRY(c, launch_token_logprob(s, a.scratch, rows_now, g.vocab, a.inv_t, a.target + r0, a.rm.pos + r0,
-                                      a.logp + r0));
+    } else {
+      // every row feeds the output projection, scratch_rows rows at a time: the
+      // [M, vocab] logits never exist as a whole
+      for (int r0 = 0; r0 < a.M; r0 += a.scratch_rows) {
+        const int rows_now = std::min(a.scratch_rows, a.M - r0);
+        {
+          ProfScope ps(c, AREAL_K_GEMM_LMHEAD, -1, sampled, (double)rows_now);
+          HIP_TRY(c, launch_gemm(s, xn + (int64_t)r0 * H, wl, a.scratch, rows_now, g.vocab, H, g.vocab,
+                                 GEMM_STORE_F32));
+        }
+        HIP_TRY(c, launch_token_logprob(s, a.scratch, rows_now, g.vocab, a.inv_t, a.target + r0, a.rm.pos + r0,
+                                        a.logp + r0));
+      }
     }
   }
   if (a.n_out > 0) {
@@ -580,6 +605,7 @@ int areal_create(const areal_model_cfg* cfg, areal_ctx** out) {
     if (v >= 64 && v <= 65536) c->split_target = v;
   }
   if (const char* e = getenv("AREAL_DECODE_GROUPS")) c->group_decode = atoi(e) > 0 ? 1 : (atoi(e) == 0 ? 0 : -1);
+  if (const char* e = getenv("AREAL_SCORE_FUSED")) c->fused_scoring = atoi(e) != 0;
   if (const char* e = getenv("AREAL_DECODE_MIN_CHUNK")) {
     const int v = atoi(e);
     if (v >= 128 && v <= 2048 && v % 128 == 0) c->min_chunk = v;

@@ -52,6 +52,28 @@ __global__ __launch_bounds__(LP_THREADS) void token_logprob_kernel(
   }
 }
 
+// Second half of the fused scoring path: the per-tile (max, sum) pairs of a row, written by the
+// output projection's epilogue as float2 [n_tiles][ld_rows], are folded and the row's log-prob
+// comes out as target_z - max - log sum.  One thread per row: for a fixed tile the rows of a
+// work-group are neighbours in memory.
+__global__ __launch_bounds__(256) void lse_finish_kernel(const float2* __restrict__ part, int ld_rows, int n_tiles,
+                                                         const float* __restrict__ target_z,
+                                                         const int32_t* __restrict__ target,
+                                                         const int32_t* __restrict__ pos, int n,
+                                                         float* __restrict__ out) {
+  const int row = blockIdx.x * 256 + threadIdx.x;
+  if (row >= n) return;
+  if (pos[row] == 0) out[row] = 0.f;                            // nothing predicts a first token
+  const int tok = target[row];
+  if (tok < 0) return;                                          // last token of its sequence
+  float m = -INFINITY, s = 0.f;
+  for (int t = 0; t < n_tiles; ++t) {
+    const float2 p = part[(int64_t)t * ld_rows + row];
+    lse_combine(m, s, p.x, p.y);
+  }
+  out[row + 1] = target_z[row] - m - __logf(s);
+}
+
 // Decoupled PPO objective, forward value: per token
 //   u = exp(lt - lp), w = exp(lp - lb), obj = w * min(u A, clip(u, 1-eps, 1+eps) A),
 // optional mask; sums[0] += sum obj, sums[1] += number of tokens whose clipped term is the
@@ -96,6 +118,16 @@ hipError_t launch_ppo_objective(hipStream_t s, int n, const float* lt, const flo
   if (n == 0) return hipSuccess;
   const int grid = std::min((n + 255) / 256, 1024);
   ppo_objective_kernel<<<grid, 256, 0, s>>>(n, lt, lp, lb, adv, mask, eps, obj_out, sums);
+  return hipGetLastError();
+}
+
+hipError_t launch_lse_finish(hipStream_t s, const void* part, int ld_rows, int n_tiles, const float* target_z,
+                             const int32_t* target, const int32_t* pos, int n, float* out) {
+  if (n <= 0 || n_tiles <= 0 || ld_rows < n || !part || !target_z || !target || !pos || !out ||
+      ((uintptr_t)part & 7))
+    return hipErrorInvalidValue;
+  lse_finish_kernel<<<(n + 255) / 256, 256, 0, s>>>(reinterpret_cast<const float2*>(part), ld_rows, n_tiles,
+                                                    target_z, target, pos, n, out);
   return hipGetLastError();
 }
 

@@ -68,6 +68,40 @@ def test_packed_sequences_match_oracle(torch, binding, temperature, scratch_rows
     eng.close()
 
 
+@pytest.mark.parametrize("vocab,scratch_rows", [(1024, 64), (1000, 700), (5000, 3)])
+def test_large_passes_fused_and_unfused_output_projection(torch, binding, vocab, scratch_rows):
+    """Passes of up to 1,000 rows: the output projection folds the log-sum-exp into its epilogue
+    (256 x 256 tiles above 256 rows, 128 x 128 below, as many rows per launch as their per-tile
+    pairs fit into the scratch), with vocabularies that end inside a tile.  Against the oracle,
+    and against the path that writes the logits of a chunk of rows and reduces them afterwards."""
+    import os
+    from oracle import scoring
+    cfg = synth.shape("tiny", vocab=vocab)
+    w = synth.random_gains(synth.make_weights(cfg, 23, qkv_bias=True, std=0.05), 3)
+    rng = np.random.default_rng(vocab)
+    lens = [700, 290, 5, 257, 130, 1, 64]
+    seqs = [rng.integers(0, vocab, size=n).astype(np.int32) for n in lens]
+    ref = scoring.batch_logprobs(seqs, _f16_weights(w), cfg, 0.8)
+    got = {}
+    saved = os.environ.get("AREAL_SCORE_FUSED")
+    try:
+        for fused in ("1", "0"):
+            os.environ["AREAL_SCORE_FUSED"] = fused
+            eng = _engine(binding, cfg, w, max_seqs=4, max_seq_len=704, max_batch_tokens=1000, kv_blocks=200)
+            got[fused] = eng.recompute_logprob(seqs, 0.8, scratch_rows).cpu().numpy()
+            assert eng.kv_blocks() == (200, 200)
+            eng.close()
+            err = np.abs(got[fused] - ref).max()
+            print(f"vocab {vocab}, fused {fused}: max |dlogp| {err:.2e}")
+            assert err <= LOGP_TOL
+    finally:
+        if saved is None:
+            os.environ.pop("AREAL_SCORE_FUSED", None)
+        else:
+            os.environ["AREAL_SCORE_FUSED"] = saved
+    assert np.abs(got["1"] - got["0"]).max() <= 2e-3        # two runs differ by the order of float32 atomic adds
+
+
 def test_scoring_leaves_live_sequences_alone_and_matches_emitted_logprobs(torch, binding):
     """Generate on the GPU, then score the finished trajectories while other
     sequences are still live: (a) the recomputed log-probs equal the untruncated
