@@ -252,7 +252,7 @@ int areal_append_tokens(areal_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
  *   logp_out[cu[i]]     = 0.
  * One causal forward over all tokens (the prefill kernels, chunks of
  * max_batch_tokens rows).  No logits are stored: the output projection leaves a
- * (max, sum of exponentials) pair per row and 256-column tile in the scratch and a
+ * (max, sum of exponentials) pair per row and column tile in the scratch and a
  * second kernel folds them (when the hidden size is not a multiple of 64 the
  * logits of scratch_rows rows at a time are written there and reduced instead).
  * Live sequences are untouched: the pass borrows unused sequence slots and free
