@@ -13,9 +13,11 @@ def _ref(A, W):
 
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (37, 344, 128), (200, 1000, 344), (256, 1536, 1536),
                                    (300, 2048, 1000), (130, 520, 8960),
-                                   (5000, 1100, 512)])   # more than 8 row tiles: the super-tile block map
+                                   (5000, 1100, 512),    # more than 8 row tiles: the super-tile block map
+                                   (8192, 1536, 640)])   # 192 tiles of 256 x 256: a partly filled last round
 def test_gemm_all_configs(M, N, K):
     NO_SWIGLU = (22, 23)      # one 32-column panel per wave: no gate/up pair in a wave
+    ADD_ONLY = (24,)          # pieces of a tile add into C with atomics: the residual-add mode only
     import torch
     from paper_2505_24298_amd import binding
     L = binding.lib()
@@ -33,14 +35,18 @@ def test_gemm_all_configs(M, N, K):
             continue
         for splits in (1, 3, -1):
             C = torch.zeros((M, N), device="cuda")
-            binding.op_gemm(A, W0, None, C, 0, cfg, splits)
-            assert np.abs(C.cpu().numpy() - ref0).max() <= 2e-5 * scale * (K ** 0.5), (cfg, splits)
+            if cfg in ADD_ONLY:
+                with pytest.raises(binding.ArealError):
+                    binding.op_gemm(A, W0, None, C, 0, cfg, splits)
+            else:
+                binding.op_gemm(A, W0, None, C, 0, cfg, splits)
+                assert np.abs(C.cpu().numpy() - ref0).max() <= 2e-5 * scale * (K ** 0.5), (cfg, splits)
             base = torch.randn((M, N), generator=g, device="cuda")
             C = base.clone()
             binding.op_gemm(A, W0, None, C, 1, cfg, splits)
             assert np.abs(C.cpu().numpy() - (base.cpu().numpy() + ref0)).max() <= 2e-5 * scale * (K ** 0.5)
         Cb = torch.zeros((M, N), device="cuda", dtype=torch.float16)
-        if cfg in NO_SWIGLU:
+        if cfg in NO_SWIGLU or cfg in ADD_ONLY:
             with pytest.raises(binding.ArealError):
                 binding.op_gemm(A, W0, W1, Cb, 2, cfg, 1)
             continue
