@@ -16,7 +16,7 @@ def _ref(A, W):
                                    (5000, 1100, 512),    # more than 8 row tiles: the super-tile block map
                                    (8192, 1536, 640)])   # 192 tiles of 256 x 256: a partly filled last round
 def test_gemm_all_configs(M, N, K):
-    NO_SWIGLU = (22, 23)      # one 32-column panel per wave: no gate/up pair in a wave
+    NO_SWIGLU = (22, 23, 25)  # one 32-column panel per wave: no gate/up pair in a wave
     ADD_ONLY = (24,)          # pieces of a tile add into C with atomics: the residual-add mode only
     import torch
     from paper_2505_24298_amd import binding
