@@ -363,3 +363,41 @@ def test_streaming_controller_follows_the_oracle_event_loop(eta):
         ticks, done = staleness.simulate_stream(n_total, B, eta, slots, outs)
         assert r["ticks"] == ticks and sorted(r["records"]) == sorted(done)
         assert r["gen_tokens"] == int(outs.sum()) and not eng.live
+
+
+def test_tile_choice_for_the_decoder_shapes(L):
+    """areal_op_gemm_choose (host only): the tile configuration and K split the library takes for
+    the products of the 1.5B and 7B shapes, at the row counts where the rules change.  Pins the
+    rules that were read off sweeps on the MI355X, so that an edit of one does not silently
+    move another: configuration numbers as in gemm.hip's dispatch."""
+    import ctypes as C
+
+    def choose(M, N, K, mode):
+        c, s = C.c_int32(), C.c_int32()
+        assert L.areal_op_gemm_choose(M, N, K, mode, C.byref(c), C.byref(s)) == 0
+        return c.value, s.value
+
+    STORE, ADD, SWIGLU = 0, 1, 2
+    H, F, V = 1536, 8960, 151936
+    # prefill passes of 8,192 rows: 256 x 256 tiles; the down projection with its last round evened out
+    assert choose(8192, 2048, H, STORE) == (19, 1)
+    assert choose(8192, F, H, SWIGLU) == (19, 1)
+    assert choose(8192, H, F, ADD) == (24, 1)
+    assert choose(8192, 3584, 18944, ADD) == (24, 1)
+    assert choose(8192, H, H, ADD)[0] == 20
+    # decode steps: gate/up by row count, no K split (the SwiGLU epilogue needs whole sums)
+    assert [choose(M, F, H, SWIGLU) for M in (24, 48, 100, 200)] == [(12, 1), (10, 1), (21, 1), (20, 1)]
+    # narrow products split K; the down projection at few rows takes 64-column tiles
+    assert choose(24, H, F, ADD) == (25, 8)
+    assert choose(100, H, F, ADD) == (23, 8)
+    for M in (8, 64, 256):
+        cfg, splits = choose(M, 2048, H, STORE)
+        assert cfg in (21, 22, 23) and 1 < splits <= 12
+    # output projection: one work-group per column panel, never split
+    assert [choose(M, V, H, STORE)[1] for M in (1, 100, 256)] == [1, 1, 1]
+    # a ragged K (not a multiple of 64) falls back to the register-staged tiles
+    assert choose(100, 1000, 344, STORE)[0] in (0, 2, 4)
+    # invalid shapes are refused
+    c, s = C.c_int32(), C.c_int32()
+    assert L.areal_op_gemm_choose(0, 8, 8, 0, C.byref(c), C.byref(s)) != 0
+    assert L.areal_op_gemm_choose(8, 8, 8, 3, C.byref(c), C.byref(s)) != 0
