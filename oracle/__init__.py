@@ -30,9 +30,10 @@ tests/test_oracle_*.py.  Parity status per function:
 
 decoder.rmsnorm, rope, attention, swiglu, forward  -- pinned (closed forms,
     brute force, invariances).
-decoder whole-model values -- parity unpinned against the outside world: no
-    trained checkpoint or reference logits exist for this build; pinned only
-    through the invariants above on synthetic weights.
+decoder whole-model values -- pinned: the full forward pass agrees with the public
+    Qwen2 model class of the `transformers` library in float64 on random weights
+    (test_forward_matches_public_qwen2_implementation); no trained checkpoint is
+    involved anywhere in this build.
 sampler.philox4x32_10 -- pinned by the known-answer vectors distributed with
     the generator's reference implementation (tests/golden/philox_kat.txt).
 sampler.sexp, mass, nucleus, draw, logprobs -- pinned (libm, exact integer
