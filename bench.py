@@ -313,6 +313,8 @@ def summarise(args, cfg, wl, n, runs, warmups_done, copy_gbs, cpu_baseline, bind
                    "hbm_frac_of_peak": round(dec_gbs / HBM_PEAK_GBS, 4),
                    "hbm_frac_of_measured_copy": None if not copy_gbs else round(dec_gbs / copy_gbs, 4),
                    "measured_copy_GBps": None if not copy_gbs else round(copy_gbs, 1),
+                   # against a kernel that only reads, at the largest launch size measured (512 MiB)
+                   "hbm_frac_of_plain_read": None if not read_curve else round(dec_gbs / read_curve[-1][1], 4),
                    "ms_per_decode_step": round(dec_ms / max(1, dec_steps), 4),
                    "attn_decode_launches": cfg["n_layers"] * dec_steps,
                    "attn_decode_kv_bytes_algorithmic": int(kv_layer_bytes * cfg["n_layers"]
