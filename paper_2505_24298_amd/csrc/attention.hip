@@ -107,7 +107,6 @@ template <int D>
 __device__ __forceinline__ void load_group_ids(KvFrag<D>& f, const f16* __restrict__ arena,
                                                const KvGeom& geom, const BlockIds& ids, int b0, int b,
                                                int b_end, int kvh, int lane) {
-  const int g = lane >> 4, j = lane & 15;
   const f16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
   for (int u = 0; u < NB; ++u) {
